@@ -1,0 +1,115 @@
+/*
+ * slimattn.h — C ABI of the SlimAttention library for AMD MI355X (gfx950).
+ *
+ * Three operations, as the paper states the problem (batch, query heads, KV heads,
+ * sequence length, head dim, causal flag, softmax scale):
+ *
+ *   kv_quant_int8          builds the reduced-precision KV cache of section 2.2
+ *   slim_attn_prefill      first-token attention of section 2.1 (score rows over all
+ *                          keys, softmax over the row, row times V), bf16 or INT8 K/V
+ *   slim_attn_decode_int8  next-token attention over the INT8 cache (section 2.2)
+ *
+ * Common rules
+ *   - Every pointer marked "device" is GPU memory owned by the caller, 16-byte
+ *     aligned, densely packed in the stated layout (last index fastest).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
+ *     enqueued on it; no call synchronises, allocates or frees, and the library keeps no
+ *     state between calls.
+ *   - Every call returns a SLIM_* status.  On any status other than SLIM_OK and
+ *     SLIM_ERR_LAUNCH nothing was enqueued.  Nothing throws across this boundary.
+ *   - bf16 = upper 16 bits of IEEE fp32.  NaN or infinity in an input gives undefined
+ *     values in the outputs that depend on it (inputs are not scanned).
+ *   - Query head h reads KV head h / (q_heads / kv_heads): consecutive query heads
+ *     share a KV head.
+ */
+#ifndef SLIMATTN_H
+#define SLIMATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    SLIM_OK = 0,
+    SLIM_ERR_NULL = 1,        /* a required pointer is NULL, or a scale pointer is inconsistent with kv_dtype */
+    SLIM_ERR_SHAPE = 2,       /* a size is <= 0, too large to index, q_heads % kv_heads != 0, bad scale/flag */
+    SLIM_ERR_UNSUPPORTED = 3, /* head_dim not in {64, 128}, or an unknown dtype code */
+    SLIM_ERR_ALIGN = 4,       /* a pointer is not 16-byte aligned */
+    SLIM_ERR_WORKSPACE = 5,   /* workspace smaller than slim_attn_decode_int8_workspace_bytes() */
+    SLIM_ERR_LAUNCH = 6       /* the HIP runtime refused a kernel launch */
+};
+
+enum { SLIM_BF16 = 0, SLIM_F32 = 1, SLIM_I8 = 2 };
+
+/*
+ * INT8 KV-cache quantiser (section 2.2: INT8 K/V with one scale per token per head).
+ * Symmetric, per row of head_dim values:
+ *     amax = max_d |x_d| ; scale = fl32(amax / 127) ; code_d = clamp(rne(fl32(x_d / scale)), -127, 127)
+ *     amax == 0  ->  scale = 0, codes = 0.      (IEEE fp32 division, ties to even)
+ * x_bf16  device, in   [batch, kv_heads, seq_len, head_dim] bf16
+ * codes   device, out  [batch, kv_heads, seq_len, head_dim] int8
+ * scales  device, out  [batch, kv_heads, seq_len] fp32
+ * q_heads, causal and softmax_scale belong to the common argument tail and are ignored.
+ */
+int kv_quant_int8(const void* x_bf16, int8_t* codes, float* scales,
+                  int batch, int q_heads, int kv_heads, int seq_len, int head_dim,
+                  int causal, float softmax_scale, void* stream);
+
+/*
+ * Prefill attention (section 2.1).  For every batch b, query head h and query row i:
+ *     s_j = softmax_scale * <q[b,h,i,:], k^[b,g,j,:]>   over the visible keys j
+ *     o[b,h,i,:] = sum_j softmax_j(s) * v^[b,g,j,:]
+ * causal != 0: key j is visible iff j <= i; causal == 0: every key.  Each work item
+ * owns a block of query rows and the whole softmax direction (the one-dimensional
+ * decomposition); K/V are streamed through it in tiles with an fp32 running max/sum.
+ * kv_dtype == SLIM_BF16: k, v are bf16 and k_scale, v_scale must be NULL.
+ * kv_dtype == SLIM_I8  : k, v are INT8 codes, k^ = code * k_scale[b,g,j] (likewise v);
+ *                        the codes are widened exactly in registers (section 2.2).
+ * q        device, in   [batch, q_heads, seq_len, head_dim] bf16
+ * k, v     device, in   [batch, kv_heads, seq_len, head_dim] bf16 or int8
+ * k_scale, v_scale  device, in  [batch, kv_heads, seq_len] fp32, or NULL
+ * out      device, out  [batch, q_heads, seq_len, head_dim], bf16 (SLIM_BF16) or fp32 (SLIM_F32)
+ * softmax_scale must be finite and > 0.
+ */
+int slim_attn_prefill(const void* q_bf16, const void* k, const void* v,
+                      const float* k_scale, const float* v_scale, void* out,
+                      int batch, int q_heads, int kv_heads, int seq_len, int head_dim,
+                      int causal, float softmax_scale, int kv_dtype, int out_dtype, void* stream);
+
+/*
+ * Bytes of device workspace slim_attn_decode_int8 needs for this shape (partial
+ * max / sum / accumulator of each split of the key axis).  0 if the shape is invalid.
+ */
+size_t slim_attn_decode_int8_workspace_bytes(int batch, int q_heads, int kv_heads, int kv_len, int head_dim);
+
+/*
+ * Decode attention over the INT8 KV cache (section 2.2: a bandwidth-bound matrix-vector
+ * product; INT8 is widened to FP32 in registers and fed to FMAs).  One query token per
+ * (batch, query head) attends to all kv_len cached tokens:
+ *     s_t = softmax_scale * k_scale[b,g,t] * <q[b,h,:], k_codes[b,g,t,:]>
+ *     o[b,h,:] = sum_t softmax_t(s) * v_scale[b,g,t] * v_codes[b,g,t,:]
+ * The query is the newest position, so `causal` 0 and 1 give the same result.
+ * q_bf16    device, in   [batch, q_heads, 1, head_dim] bf16
+ * k_codes, v_codes  device, in  [batch, kv_heads, kv_len, head_dim] int8
+ * k_scale, v_scale  device, in  [batch, kv_heads, kv_len] fp32
+ * out_bf16  device, out  [batch, q_heads, 1, head_dim] bf16
+ * workspace device, scratch, at least slim_attn_decode_int8_workspace_bytes(...) bytes;
+ *           contents before and after the call are meaningless.
+ * The result does not depend on the order in which workgroups finish.
+ */
+int slim_attn_decode_int8(const void* q_bf16, const int8_t* k_codes, const float* k_scale,
+                          const int8_t* v_codes, const float* v_scale, void* out_bf16,
+                          void* workspace, size_t workspace_bytes,
+                          int batch, int q_heads, int kv_heads, int kv_len, int head_dim,
+                          int causal, float softmax_scale, void* stream);
+
+/* Name of a status code; pointer to static storage, never NULL. */
+const char* slim_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLIMATTN_H */

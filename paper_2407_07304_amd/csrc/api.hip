@@ -1,0 +1,131 @@
+// C ABI of the library (declared in include/slimattn.h): argument validation and
+// dispatch only.  Nothing here allocates, synchronises or keeps state.
+#include "../../include/slimattn.h"
+
+#include <math.h>
+
+#include "slim_kernels.h"
+
+namespace {
+
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+// Total element counts must stay indexable with the 32-bit row counters the kernels use.
+inline bool too_large(long a, long b, long c) {
+    const long lim = 2147483647L;
+    if (a > lim || b > lim || c > lim) return true;
+    if (a * b > lim) return true;
+    return a * b * c > lim;
+}
+
+int check_shape(int batch, int q_heads, int kv_heads, int len, int head_dim) {
+    if (batch <= 0 || q_heads <= 0 || kv_heads <= 0 || len <= 0 || head_dim <= 0) return SLIM_ERR_SHAPE;
+    if (q_heads % kv_heads != 0) return SLIM_ERR_SHAPE;
+    if (head_dim != 64 && head_dim != 128) return SLIM_ERR_UNSUPPORTED;
+    if (too_large(batch, q_heads, len)) return SLIM_ERR_SHAPE;   // rows of Q/O (and of K/V, kv_heads <= q_heads)
+    if (q_heads > 65535 || batch > 65535) return SLIM_ERR_SHAPE;
+    return SLIM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* slim_status_string(int status) {
+    switch (status) {
+        case SLIM_OK: return "SLIM_OK";
+        case SLIM_ERR_NULL: return "SLIM_ERR_NULL: required pointer is null or scale pointers do not match kv_dtype";
+        case SLIM_ERR_SHAPE: return "SLIM_ERR_SHAPE: invalid size, head ratio, flag or softmax scale";
+        case SLIM_ERR_UNSUPPORTED: return "SLIM_ERR_UNSUPPORTED: head_dim must be 64 or 128 and dtype codes must be known";
+        case SLIM_ERR_ALIGN: return "SLIM_ERR_ALIGN: pointers must be 16-byte aligned";
+        case SLIM_ERR_WORKSPACE: return "SLIM_ERR_WORKSPACE: workspace too small";
+        case SLIM_ERR_LAUNCH: return "SLIM_ERR_LAUNCH: kernel launch failed";
+        default: return "unknown status";
+    }
+}
+
+int kv_quant_int8(const void* x_bf16, int8_t* codes, float* scales, int batch, int q_heads, int kv_heads, int seq_len,
+                  int head_dim, int causal, float softmax_scale, void* stream) {
+    (void)q_heads;
+    (void)causal;
+    (void)softmax_scale;
+    if (!x_bf16 || !codes || !scales) return SLIM_ERR_NULL;
+    const int st = check_shape(batch, kv_heads, kv_heads, seq_len, head_dim);
+    if (st != SLIM_OK) return st;
+    if (misaligned(x_bf16) || misaligned(codes) || misaligned(scales)) return SLIM_ERR_ALIGN;
+    const long n_rows = (long)batch * kv_heads * seq_len;
+    const hipError_t e = slim::launch_kv_quant_int8(x_bf16, codes, scales, n_rows, head_dim, (hipStream_t)stream);
+    return e == hipSuccess ? SLIM_OK : SLIM_ERR_LAUNCH;
+}
+
+int slim_attn_prefill(const void* q_bf16, const void* k, const void* v, const float* k_scale, const float* v_scale,
+                      void* out, int batch, int q_heads, int kv_heads, int seq_len, int head_dim, int causal,
+                      float softmax_scale, int kv_dtype, int out_dtype, void* stream) {
+    if (!q_bf16 || !k || !v || !out) return SLIM_ERR_NULL;
+    if (kv_dtype != SLIM_BF16 && kv_dtype != SLIM_I8) return SLIM_ERR_UNSUPPORTED;
+    if (out_dtype != SLIM_BF16 && out_dtype != SLIM_F32) return SLIM_ERR_UNSUPPORTED;
+    if (kv_dtype == SLIM_I8 && (!k_scale || !v_scale)) return SLIM_ERR_NULL;
+    if (kv_dtype == SLIM_BF16 && (k_scale || v_scale)) return SLIM_ERR_NULL;
+    const int st = check_shape(batch, q_heads, kv_heads, seq_len, head_dim);
+    if (st != SLIM_OK) return st;
+    if (causal != 0 && causal != 1) return SLIM_ERR_SHAPE;
+    if (!(softmax_scale > 0.0f) || !isfinite(softmax_scale)) return SLIM_ERR_SHAPE;
+    if (misaligned(q_bf16) || misaligned(k) || misaligned(v) || misaligned(out)) return SLIM_ERR_ALIGN;
+    if (kv_dtype == SLIM_I8 && (misaligned(k_scale) || misaligned(v_scale))) return SLIM_ERR_ALIGN;
+    slim::PrefillArgs a;
+    a.q = q_bf16;
+    a.k = k;
+    a.v = v;
+    a.k_scale = k_scale;
+    a.v_scale = v_scale;
+    a.out = out;
+    a.batch = batch;
+    a.q_heads = q_heads;
+    a.kv_heads = kv_heads;
+    a.seq_len = seq_len;
+    a.head_dim = head_dim;
+    a.causal = causal;
+    a.softmax_scale = softmax_scale;
+    a.kv_int8 = kv_dtype == SLIM_I8;
+    a.out_f32 = out_dtype == SLIM_F32;
+    const hipError_t e = slim::launch_prefill(a, (hipStream_t)stream);
+    return e == hipSuccess ? SLIM_OK : SLIM_ERR_LAUNCH;
+}
+
+size_t slim_attn_decode_int8_workspace_bytes(int batch, int q_heads, int kv_heads, int kv_len, int head_dim) {
+    if (check_shape(batch, q_heads, kv_heads, kv_len, head_dim) != SLIM_OK) return 0;
+    return slim::decode_workspace_bytes(batch, q_heads, kv_len, head_dim);
+}
+
+int slim_attn_decode_int8(const void* q_bf16, const int8_t* k_codes, const float* k_scale, const int8_t* v_codes,
+                          const float* v_scale, void* out_bf16, void* workspace, size_t workspace_bytes, int batch,
+                          int q_heads, int kv_heads, int kv_len, int head_dim, int causal, float softmax_scale,
+                          void* stream) {
+    if (!q_bf16 || !k_codes || !k_scale || !v_codes || !v_scale || !out_bf16 || !workspace) return SLIM_ERR_NULL;
+    const int st = check_shape(batch, q_heads, kv_heads, kv_len, head_dim);
+    if (st != SLIM_OK) return st;
+    if (causal != 0 && causal != 1) return SLIM_ERR_SHAPE;
+    if (!(softmax_scale > 0.0f) || !isfinite(softmax_scale)) return SLIM_ERR_SHAPE;
+    if (misaligned(q_bf16) || misaligned(k_codes) || misaligned(k_scale) || misaligned(v_codes) ||
+        misaligned(v_scale) || misaligned(out_bf16) || misaligned(workspace))
+        return SLIM_ERR_ALIGN;
+    if (workspace_bytes < slim::decode_workspace_bytes(batch, q_heads, kv_len, head_dim)) return SLIM_ERR_WORKSPACE;
+    slim::DecodeArgs a;
+    a.q = q_bf16;
+    a.k_codes = k_codes;
+    a.k_scale = k_scale;
+    a.v_codes = v_codes;
+    a.v_scale = v_scale;
+    a.out = out_bf16;
+    a.workspace = (float*)workspace;
+    a.batch = batch;
+    a.q_heads = q_heads;
+    a.kv_heads = kv_heads;
+    a.kv_len = kv_len;
+    a.head_dim = head_dim;
+    a.softmax_scale = softmax_scale;
+    const hipError_t e = slim::launch_decode(a, (hipStream_t)stream);
+    return e == hipSuccess ? SLIM_OK : SLIM_ERR_LAUNCH;
+}
+
+}  // extern "C"

@@ -1,0 +1,67 @@
+// INT8 KV-cache quantiser (paper section 2.2: INT8 K/V, one scale per token per head).
+//
+// One row of D bf16 values (one token of one head) is held by D/8 adjacent lanes, 16
+// bytes each.  amax is reduced across those lanes, scale = amax / 127 and
+// code = rint(x / scale) use IEEE fp32 division (correctly rounded, denormals kept) so
+// that codes and scales are reproducible bit for bit on any IEEE machine.
+// Streaming kernel: 2 B read + 1 B written per element, plus 4 B per row.
+#include "slim_common.h"
+#include "slim_kernels.h"
+
+namespace slim {
+
+template <int D>
+__global__ __launch_bounds__(256) void kv_quant_int8_kernel(const uint16_t* __restrict__ x, int8_t* __restrict__ codes,
+                                                            float* __restrict__ scales, long n_rows) {
+    constexpr int LPR = D / 8;           // lanes per row
+    constexpr int ROWS = 256 / LPR;      // rows per workgroup pass
+    const int lane_in_row = threadIdx.x % LPR;
+    const long row0 = (long)blockIdx.x * ROWS + threadIdx.x / LPR;
+    const long stride = (long)gridDim.x * ROWS;
+    for (long row = row0; row < n_rows; row += stride) {   // rows past the end leave whole row groups idle together
+        const u32x4 raw = *reinterpret_cast<const u32x4*>(x + row * D + lane_in_row * 8);
+        float v[8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = bf16_bits_to_f32(raw[i] & 0xffffu);
+            v[2 * i + 1] = __uint_as_float(raw[i] & 0xffff0000u);
+        }
+        float amax = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(v[i]));
+#pragma unroll
+        for (int off = 1; off < LPR; off <<= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
+        const float scale = amax / 127.0f;   // IEEE division, one rounding
+        unsigned int packed[2] = {0u, 0u};
+        if (amax != 0.0f) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                float r = rintf(v[i] / scale);   // IEEE division, then ties-to-even
+                r = fminf(fmaxf(r, -127.0f), 127.0f);
+                packed[i / 4] |= ((unsigned int)(int)r & 0xffu) << (8 * (i % 4));
+            }
+        }
+        u32x2 out2;
+        out2[0] = packed[0];
+        out2[1] = packed[1];
+        *reinterpret_cast<u32x2*>(codes + row * D + lane_in_row * 8) = out2;
+        if (lane_in_row == 0) scales[row] = scale;
+    }
+}
+
+hipError_t launch_kv_quant_int8(const void* x, int8_t* codes, float* scales, long n_rows, int head_dim,
+                                hipStream_t stream) {
+    const int rows_per_block = 256 / (head_dim / 8);
+    long blocks = (n_rows + rows_per_block - 1) / rows_per_block;
+    const long max_blocks = 256L * 64;   // 256 CUs; beyond this the grid-stride loop takes over
+    if (blocks > max_blocks) blocks = max_blocks;
+    if (head_dim == 128)
+        hipLaunchKernelGGL(kv_quant_int8_kernel<128>, dim3((unsigned)blocks), dim3(256), 0, stream,
+                           (const uint16_t*)x, codes, scales, n_rows);
+    else
+        hipLaunchKernelGGL(kv_quant_int8_kernel<64>, dim3((unsigned)blocks), dim3(256), 0, stream,
+                           (const uint16_t*)x, codes, scales, n_rows);
+    return hipGetLastError();
+}
+
+}  // namespace slim

@@ -1,0 +1,42 @@
+// Host-side launchers of the gfx950 kernels; arguments are validated by the C ABI layer.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace slim {
+
+hipError_t launch_kv_quant_int8(const void* x, int8_t* codes, float* scales, long n_rows, int head_dim,
+                                hipStream_t stream);
+
+struct PrefillArgs {
+    const void* q;
+    const void* k;
+    const void* v;
+    const float* k_scale;
+    const float* v_scale;
+    void* out;
+    int batch, q_heads, kv_heads, seq_len, head_dim, causal;
+    float softmax_scale;
+    bool kv_int8, out_f32;
+};
+hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream);
+
+struct DecodeArgs {
+    const void* q;
+    const int8_t* k_codes;
+    const float* k_scale;
+    const int8_t* v_codes;
+    const float* v_scale;
+    void* out;
+    float* workspace;
+    int batch, q_heads, kv_heads, kv_len, head_dim;
+    float softmax_scale;
+};
+// Tokens of the key axis one workgroup of the split kernel covers, and the split count.
+int decode_tokens_per_split(int head_dim);
+int decode_num_splits(int kv_len, int head_dim);
+size_t decode_workspace_bytes(int batch, int q_heads, int kv_len, int head_dim);
+hipError_t launch_decode(const DecodeArgs& a, hipStream_t stream);
+
+}  // namespace slim

@@ -1,0 +1,93 @@
+"""CPU-only checks of the C ABI: the library loads, exports every declared symbol, and
+rejects bad arguments before anything is launched (no GPU is touched)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "slimattn.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2407_07304_amd import slimattn, build
+    if not os.path.exists(slimattn.LIB_PATH):
+        build.build()
+    return slimattn.load()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b([a-z_0-9]+)\s*\(", text)) - {"defined"})
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert {"kv_quant_int8", "slim_attn_prefill", "slim_attn_decode_int8",
+            "slim_attn_decode_int8_workspace_bytes", "slim_status_string"} <= set(names)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_status_strings(lib):
+    seen = set()
+    for code in range(7):
+        s = lib.slim_status_string(code).decode()
+        assert s and s not in seen
+        seen.add(s)
+    assert lib.slim_status_string(99).decode() == "unknown status"
+
+
+P = ctypes.c_void_p
+A = 0x1000   # a fake, aligned, never dereferenced address: every case below fails validation first
+
+
+def prefill(lib, q=A, k=A, v=A, ks=None, vs=None, out=A, B=1, Hq=2, Hkv=2, S=16, D=128, causal=1, scale=0.1,
+            kvd=0, od=0):
+    return lib.slim_attn_prefill(P(q), P(k), P(v), P(ks), P(vs), P(out), B, Hq, Hkv, S, D, causal, scale, kvd, od, None)
+
+
+def test_prefill_rejects_bad_arguments(lib):
+    NULL, SHAPE, UNSUP, ALIGN = 1, 2, 3, 4
+    assert prefill(lib, q=None) == NULL
+    assert prefill(lib, out=None) == NULL
+    assert prefill(lib, kvd=2) == NULL                 # INT8 without scales
+    assert prefill(lib, ks=A, vs=A) == NULL            # bf16 with scales
+    assert prefill(lib, kvd=1) == UNSUP and prefill(lib, od=2) == UNSUP
+    assert prefill(lib, D=96) == UNSUP
+    assert prefill(lib, S=0) == SHAPE and prefill(lib, B=-1) == SHAPE
+    assert prefill(lib, Hq=3, Hkv=2) == SHAPE
+    assert prefill(lib, causal=2) == SHAPE
+    assert prefill(lib, scale=0.0) == SHAPE and prefill(lib, scale=float("nan")) == SHAPE
+    assert prefill(lib, scale=float("inf")) == SHAPE
+    assert prefill(lib, k=A + 8) == ALIGN
+    assert prefill(lib, kvd=2, ks=A + 4, vs=A) == ALIGN
+    assert prefill(lib, B=65536, Hq=65536, Hkv=65536, S=4096) == SHAPE   # not indexable
+
+
+def test_quant_rejects_bad_arguments(lib):
+    f = lib.kv_quant_int8
+    assert f(P(None), P(A), P(A), 1, 1, 1, 4, 128, 0, 1.0, None) == 1
+    assert f(P(A), P(A), P(A), 1, 1, 1, 0, 128, 0, 1.0, None) == 2
+    assert f(P(A), P(A), P(A), 1, 1, 1, 4, 100, 0, 1.0, None) == 3
+    assert f(P(A), P(A + 1), P(A), 1, 1, 1, 4, 128, 0, 1.0, None) == 4
+
+
+def test_decode_rejects_bad_arguments_and_reports_workspace(lib):
+    ws = lib.slim_attn_decode_int8_workspace_bytes
+    assert ws(16, 32, 32, 8192, 128) == 16 * 32 * 8 * (128 + 2) * 4
+    assert ws(1, 1, 1, 1, 64) == (64 + 2) * 4
+    assert ws(1, 3, 2, 10, 128) == 0 and ws(1, 1, 1, 10, 96) == 0
+    f = lib.slim_attn_decode_int8
+
+    def call(q=A, kc=A, ks=A, vc=A, vs=A, out=A, wsp=A, wsb=1 << 30, B=1, Hq=2, Hkv=2, T=100, D=128, causal=0, scale=0.1):
+        return f(P(q), P(kc), P(ks), P(vc), P(vs), P(out), P(wsp), wsb, B, Hq, Hkv, T, D, causal, scale, None)
+
+    assert call(vs=None) == 1 and call(wsp=None) == 1
+    assert call(T=0) == 2 and call(Hq=4, Hkv=3) == 2 and call(scale=-1.0) == 2
+    assert call(D=32) == 3
+    assert call(out=A + 2) == 4
+    assert call(wsb=(2 * (128 + 2) * 4) - 1) == 5

@@ -1,0 +1,218 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element by element.
+
+INT8 codes and scales must match bit for bit; attention outputs must stay within
+max-abs 2e-2 and mean-abs 2e-3 of the fp64 oracle.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2407_07304_amd import inputs
+from paper_2407_07304_amd.inputs import WORKLOADS, normal_bf16, f32_to_bf16_bits
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def sa():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2407_07304_amd import slimattn
+    slimattn.load()
+    return slimattn
+
+
+from _gpu_util import dev, dev_bf16, host_f64, check_close  # noqa: E402
+
+
+# ---------------------------------------------------------------- quantiser
+
+def _quant_both(sa, oracle, bits):
+    codes, scales = sa.kv_quant_int8(dev_bf16(bits))
+    torch.cuda.synchronize()
+    want_c, want_s = oracle.kv_quant_int8(bits)
+    got_c, got_s = codes.cpu().numpy(), scales.cpu().numpy()
+    assert np.array_equal(got_s.view(np.uint32), want_s.view(np.uint32)), "scales differ"
+    assert np.array_equal(got_c, want_c), "codes differ"
+
+
+@pytest.mark.parametrize("shape", [(2, 3, 301, 128), (1, 2, 77, 64), (1, 1, 1, 128), (3, 5, 1000, 64)])
+def test_kv_quant_bit_exact_normal(sa, oracle, shape):
+    print("kv_quant", shape, flush=True)
+    _quant_both(sa, oracle, normal_bf16(np.random.default_rng(31), shape))
+
+
+def test_kv_quant_bit_exact_special_rows(sa, oracle):
+    rng = np.random.default_rng(32)
+    bits = normal_bf16(rng, (1, 4, 64, 128))
+    bits[0, 0, 0] = 0                                                     # all-zero row
+    bits[0, 0, 1] = rng.integers(0, 0x0080, 128).astype(np.uint16)        # bf16 subnormals
+    bits[0, 0, 2] = rng.integers(0, 0x7f80, 128).astype(np.uint16)        # any magnitude
+    halves = np.array([0.5, 1.5, 2.5, 3.5, -0.5, -1.5, -2.5, 126.5, -126.5, 127.0], dtype=np.float32)
+    row = np.zeros(128, dtype=np.float32)
+    row[:10] = halves
+    bits[0, 0, 3] = f32_to_bf16_bits(row)                                 # exact ties at scale 1
+    bits[0, 0, 4] = f32_to_bf16_bits(row / 1024)
+    bits[0, 1] = f32_to_bf16_bits((rng.standard_normal((64, 128)) * 1e-30).astype(np.float32))
+    bits[0, 2] = f32_to_bf16_bits((rng.standard_normal((64, 128)) * 1e30).astype(np.float32))
+    print("kv_quant special rows", flush=True)
+    _quant_both(sa, oracle, bits)
+
+
+@pytest.mark.timeout(600)
+def test_kv_quant_bit_exact_c3_shape(sa, oracle):
+    w = WORKLOADS["C3"]
+    print("kv_quant C3 K tensor", flush=True)
+    _quant_both(sa, oracle, normal_bf16(np.random.default_rng(w.seed), (w.batch, w.kv_heads, w.seq_len, w.head_dim)))
+
+
+# ---------------------------------------------------------------- prefill
+
+def _prefill_case(sa, oracle, B, Hq, Hkv, S, D, causal, kv_int8, out_f32, seed, rows=None):
+    rng = np.random.default_rng(seed)
+    q = normal_bf16(rng, (B, Hq, S, D))
+    k = normal_bf16(rng, (B, Hkv, S, D))
+    v = normal_bf16(rng, (B, Hkv, S, D))
+    scale = 1.0 / math.sqrt(D)
+    od = torch.float32 if out_f32 else torch.bfloat16
+    if kv_int8:
+        kc, ks = oracle.kv_quant_int8(k)
+        vc, vs = oracle.kv_quant_int8(v)
+        out = sa.slim_attn_prefill(dev_bf16(q), dev(kc), dev(vc), scale, causal, k_scale=dev(ks), v_scale=dev(vs),
+                                   out_dtype=od)
+        torch.cuda.synchronize()
+        want = oracle.attn(q, kc, vc, scale, causal, k_scale=ks, v_scale=vs, rows=rows)
+    else:
+        out = sa.slim_attn_prefill(dev_bf16(q), dev_bf16(k), dev_bf16(v), scale, causal, out_dtype=od)
+        torch.cuda.synchronize()
+        want = oracle.attn(q, k, v, scale, causal, rows=rows)
+    got = host_f64(out)
+    if rows is not None:
+        got = got[:, :, rows, :]
+    return check_close(got, want, "prefill B%d Hq%d Hkv%d S%d D%d causal%d int8%d" % (B, Hq, Hkv, S, D, causal, kv_int8))
+
+
+SMALL = [
+    # B, Hq, Hkv, S, D
+    (1, 2, 2, 1, 128), (1, 2, 1, 5, 64), (2, 4, 2, 127, 128), (1, 2, 2, 128, 64), (1, 4, 1, 129, 128),
+    (1, 2, 2, 200, 128), (2, 3, 3, 333, 64), (1, 8, 2, 640, 128), (1, 2, 2, 1000, 64),
+]
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,S,D", SMALL)
+@pytest.mark.parametrize("causal", [True, False])
+@pytest.mark.parametrize("kv_int8", [False, True])
+def test_prefill_small_shapes(sa, oracle, B, Hq, Hkv, S, D, causal, kv_int8):
+    print("prefill", B, Hq, Hkv, S, D, causal, kv_int8, flush=True)
+    _prefill_case(sa, oracle, B, Hq, Hkv, S, D, causal, kv_int8, out_f32=(S % 2 == 1), seed=40 + S)
+
+
+def test_prefill_c1_full(sa, oracle):
+    w = WORKLOADS["C1"]
+    print("prefill C1 full tensor", flush=True)
+    _prefill_case(sa, oracle, w.batch, w.q_heads, w.kv_heads, w.seq_len, w.head_dim, True, False, True, w.seed)
+
+
+def test_prefill_causal_row0_is_v0(sa):
+    rng = np.random.default_rng(45)
+    q, k, v = normal_bf16(rng, (1, 4, 300, 128)), normal_bf16(rng, (1, 4, 300, 128)), normal_bf16(rng, (1, 4, 300, 128))
+    out = sa.slim_attn_prefill(dev_bf16(q), dev_bf16(k), dev_bf16(v), 0.1, True)
+    torch.cuda.synchronize()
+    assert torch.equal(out[:, :, 0, :].cpu(), dev_bf16(v)[:, :, 0, :].cpu())
+
+
+def _sample_rows(S, n_random, seed):
+    rng = np.random.default_rng(seed)
+    fixed = [0, 1, 31, 32, 63, 64, 127, 128, 129, S // 2, S - 129, S - 128, S - 2, S - 1]
+    rows = sorted(set([r for r in fixed if 0 <= r < S] + rng.integers(0, S, n_random).tolist()))
+    return np.array(rows, dtype=np.int32)
+
+
+@pytest.mark.timeout(600)
+def test_prefill_c2_full_size(sa, oracle):
+    w = WORKLOADS["C2"]
+    print("prefill C2 (sampled rows of every head)", flush=True)
+    _prefill_case(sa, oracle, w.batch, w.q_heads, w.kv_heads, w.seq_len, w.head_dim, True, False, False, w.seed,
+                  rows=_sample_rows(w.seq_len, 100, 2))
+
+
+@pytest.mark.timeout(600)
+def test_prefill_c3_full_size(sa, oracle):
+    w = WORKLOADS["C3"]
+    print("prefill C3 (sampled rows of every head)", flush=True)
+    _prefill_case(sa, oracle, w.batch, w.q_heads, w.kv_heads, w.seq_len, w.head_dim, True, True, False, w.seed,
+                  rows=_sample_rows(w.seq_len, 60, 3))
+
+
+@pytest.mark.timeout(600)
+def test_prefill_c5_full_size(sa, oracle):
+    w = WORKLOADS["C5"]
+    print("prefill C5 (sampled rows of every head)", flush=True)
+    _prefill_case(sa, oracle, w.batch, w.q_heads, w.kv_heads, w.seq_len, w.head_dim, True, True, False, w.seed,
+                  rows=_sample_rows(w.seq_len, 20, 5))
+
+
+# ---------------------------------------------------------------- decode
+
+def _decode_case(sa, oracle, B, Hq, Hkv, T, D, seed):
+    rng = np.random.default_rng(seed)
+    q = normal_bf16(rng, (B, Hq, 1, D))
+    k = normal_bf16(rng, (B, Hkv, T, D))
+    v = normal_bf16(rng, (B, Hkv, T, D))
+    kc, ks = oracle.kv_quant_int8(k)
+    vc, vs = oracle.kv_quant_int8(v)
+    del k, v
+    scale = 1.0 / math.sqrt(D)
+    dq, dkc, dks, dvc, dvs = dev_bf16(q), dev(kc), dev(ks), dev(vc), dev(vs)
+    out = sa.slim_attn_decode_int8(dq, dkc, dks, dvc, dvs, scale)
+    out2 = sa.slim_attn_decode_int8(dq, dkc, dks, dvc, dvs, scale, causal=True)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2), "decode must be deterministic and ignore the causal flag"
+    want = oracle.attn(q, kc, vc, scale, False, k_scale=ks, v_scale=vs)
+    return check_close(host_f64(out), want, "decode B%d Hq%d Hkv%d T%d D%d" % (B, Hq, Hkv, T, D))
+
+
+@pytest.mark.parametrize("T", [1, 7, 255, 256, 257, 1000, 1024, 1025, 3000, 5121])
+@pytest.mark.parametrize("D,Hq,Hkv", [(128, 4, 4), (64, 4, 2), (128, 8, 1)])
+def test_decode_small_shapes(sa, oracle, T, D, Hq, Hkv):
+    print("decode", T, D, Hq, Hkv, flush=True)
+    _decode_case(sa, oracle, 2, Hq, Hkv, T, D, 50 + T)
+
+
+@pytest.mark.timeout(600)
+def test_decode_c4_full_size(sa, oracle):
+    w = WORKLOADS["C4"]
+    print("decode C4 full tensor", flush=True)
+    _decode_case(sa, oracle, w.batch, w.q_heads, w.kv_heads, w.seq_len, w.head_dim, w.seed)
+
+
+def test_decode_equals_last_prefill_row(sa, oracle):
+    rng = np.random.default_rng(60)
+    B, H, T, D = 1, 4, 777, 128
+    q, k, v = normal_bf16(rng, (B, H, T, D)), normal_bf16(rng, (B, H, T, D)), normal_bf16(rng, (B, H, T, D))
+    kc, ks = oracle.kv_quant_int8(k)
+    vc, vs = oracle.kv_quant_int8(v)
+    scale = 1.0 / math.sqrt(D)
+    pre = sa.slim_attn_prefill(dev_bf16(q), dev(kc), dev(vc), scale, True, k_scale=dev(ks), v_scale=dev(vs))
+    dec = sa.slim_attn_decode_int8(dev_bf16(np.ascontiguousarray(q[:, :, T - 1:T])), dev(kc), dev(ks), dev(vc), dev(vs), scale)
+    torch.cuda.synchronize()
+    diff = (pre[:, :, T - 1].float() - dec[:, :, 0].float()).abs().max().item()
+    assert diff <= 2e-2, diff
+
+
+# ---------------------------------------------------------------- quantise -> attend, all on the GPU
+
+def test_gpu_quantiser_feeds_gpu_attention(sa, oracle):
+    rng = np.random.default_rng(61)
+    B, Hq, Hkv, S, D = 1, 4, 2, 500, 128
+    q, k, v = normal_bf16(rng, (B, Hq, S, D)), normal_bf16(rng, (B, Hkv, S, D)), normal_bf16(rng, (B, Hkv, S, D))
+    kc, ks = sa.kv_quant_int8(dev_bf16(k))
+    vc, vs = sa.kv_quant_int8(dev_bf16(v))
+    scale = 1.0 / math.sqrt(D)
+    out = sa.slim_attn_prefill(dev_bf16(q), kc, vc, scale, True, k_scale=ks, v_scale=vs)
+    torch.cuda.synchronize()
+    okc, oks = oracle.kv_quant_int8(k)
+    ovc, ovs = oracle.kv_quant_int8(v)
+    want = oracle.attn(q, okc, ovc, scale, True, k_scale=oks, v_scale=ovs)
+    check_close(host_f64(out), want, "quantise -> prefill")
