@@ -1,0 +1,217 @@
+#!/usr/bin/env python3
+"""Benchmark of the SlimAttention hot path on one MI355X.
+
+One step = one pass of the whole path over seeded synthetic inputs already resident in HBM:
+  1. slim_attn_prefill   causal prefill, Llama-2-7B shape (B=1, 32 heads, S=2048, D=128, bf16)
+  2. kv_quant_int8       the prompt's K and V -> INT8 cache (+ one fp32 scale per token per head)
+  3. slim_attn_decode_int8  one decode step, B=16, 32 heads, D=128, INT8 cache of 8192 tokens
+
+`value` is the prefill throughput in TFLOP/s (causal flop count) and `decode.value` the
+decode throughput in GB/s (algorithmic bytes), each from HIP-event timing of its own
+kernel(s) inside the timed steps.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
+
+PAPER_TABLE3_MS = {2048: 96.65, 4096: 392.80}   # SlimAttention, 1 socket Xeon 8563C (paper Table 3); context only
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the INT8 prefill workloads reported beside the headline")
+    ap.add_argument("--only", choices=["all", "prefill", "decode", "quant"], default="all",
+                    help="run only one kernel per step (for profiling); the JSON line then carries only its fields")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (nothing on the path needs a second); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2407_07304_amd import slimattn as sa
+    from paper_2407_07304_amd import accounting as acct
+    from paper_2407_07304_amd.inputs import WORKLOADS, make_qkv
+
+    sa.load()   # raises if the HIP library has not been built: there is no fallback
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    dev_name = torch.cuda.get_device_name(0)
+
+    def dev_bf16(bits):
+        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+    c2, c4 = WORKLOADS["C2"], WORKLOADS["C4"]
+    do_prefill = args.only in ("all", "prefill")
+    do_quant = args.only in ("all", "quant")
+    do_decode = args.only in ("all", "decode")
+
+    # ---- inputs (host-seeded, then resident in HBM)
+    q2h, k2h, v2h = make_qkv(c2)
+    q2, k2, v2 = dev_bf16(q2h), dev_bf16(k2h), dev_bf16(v2h)
+    o2 = torch.empty_like(q2)
+    kc2 = torch.empty(k2.shape, dtype=torch.int8, device="cuda")
+    vc2 = torch.empty_like(kc2)
+    ks2 = torch.empty(k2.shape[:-1], dtype=torch.float32, device="cuda")
+    vs2 = torch.empty_like(ks2)
+    if do_decode:
+        q4h, k4h, v4h = make_qkv(c4)
+        q4 = dev_bf16(q4h)
+        kc4, ks4 = sa.kv_quant_int8(dev_bf16(k4h))
+        del k4h
+        vc4, vs4 = sa.kv_quant_int8(dev_bf16(v4h))
+        del v4h
+        o4 = torch.empty_like(q4)
+        ws4 = torch.empty((sa.slim_attn_decode_int8_workspace_bytes(c4.batch, c4.q_heads, c4.kv_heads, c4.seq_len,
+                                                                    c4.head_dim),), dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+
+    def step(ev=None):
+        if ev is not None:
+            ev[0].record()
+        if do_prefill:
+            sa.slim_attn_prefill(q2, k2, v2, c2.softmax_scale, True, out=o2)
+        if ev is not None:
+            ev[1].record()
+        if do_quant:
+            sa.kv_quant_int8(k2, kc2, ks2)
+            sa.kv_quant_int8(v2, vc2, vs2)
+        if ev is not None:
+            ev[2].record()
+        if do_decode:
+            sa.slim_attn_decode_int8(q4, kc4, ks4, vc4, vs4, c4.softmax_scale, out=o4, workspace=ws4)
+        if ev is not None:
+            ev[3].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ms_per_step = wall_ms / args.steps
+    seg = np.array([[e[j].elapsed_time(e[j + 1]) for j in range(3)] for e in events])   # ms: prefill, quant x2, decode
+    pre_ms, quant_ms, dec_ms = seg.mean(axis=0)
+    pre_min, quant_min, dec_min = seg.min(axis=0)
+
+    line = {
+        "metric": "prefill attn TFLOP/s + INT8-KV decode HBM GB/s, % of MI355X peak",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "device": dev_name,
+    }
+
+    pre_flops = acct.prefill_flops(c2.batch, c2.q_heads, c2.seq_len, c2.head_dim, True)
+    if do_prefill:
+        tfl = pre_flops / (pre_ms * 1e-3) / 1e12
+        line.update({
+            "value": round(tfl, 2), "unit": "TFLOP/s",
+            "prefill": {"workload": "C2", "ms": round(float(pre_ms), 4), "ms_min": round(float(pre_min), 4),
+                        "tflops": round(tfl, 2), "frac_of_bf16_mfma_peak": round(tfl / PEAK_BF16_TFLOPS, 4),
+                        "flops": pre_flops,
+                        "paper_cpu_ms_context": PAPER_TABLE3_MS[2048]},
+            "roofline": {"kernel": "slim_prefill_kernel<128,bf16 kv,bf16 out>", "bound": "mfma", "achieved": round(tfl, 2),
+                         "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tfl / PEAK_BF16_TFLOPS, 4),
+                         "traffic": None},
+        })
+    if do_decode:
+        dbytes = acct.decode_bytes(c4.batch, c4.q_heads, c4.kv_heads, c4.seq_len, c4.head_dim)
+        gbps = dbytes / (dec_ms * 1e-3) / 1e9
+        line["decode"] = {"workload": "C4", "value": round(gbps, 1), "unit": "GB/s", "ms": round(float(dec_ms), 4),
+                          "ms_min": round(float(dec_min), 4), "bytes": dbytes,
+                          "frac_of_hbm_peak": round(gbps / PEAK_HBM_GBPS, 4)}
+        line["roofline_decode"] = {"kernel": "slim_decode_int8_split_kernel<128> + slim_decode_combine_kernel<128>",
+                                   "bound": "hbm", "achieved": round(gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                                   "frac": round(gbps / PEAK_HBM_GBPS, 4), "traffic": None}
+        if not do_prefill:
+            line.update({"value": round(gbps, 1), "unit": "GB/s"})
+    if do_quant:
+        qbytes = 2 * acct.kv_quant_bytes(c2.batch * c2.kv_heads * c2.seq_len, c2.head_dim)
+        qg = qbytes / (quant_ms * 1e-3) / 1e9
+        line["kv_quant"] = {"workload": "K and V of C2", "ms": round(float(quant_ms), 4), "GBps": round(qg, 1),
+                            "bytes": qbytes, "frac_of_hbm_peak": round(qg / PEAK_HBM_GBPS, 4)}
+        if not (do_prefill or do_decode):
+            line.update({"value": round(qg, 1), "unit": "GB/s"})
+    line["config"] = {
+        "workload": "C2 causal prefill B=1 Hq=Hkv=32 S=2048 D=128 bf16 (value); then K,V -> INT8 cache; then "
+                    "C4 decode B=16 H=32 D=128 T=8192 INT8 KV (decode.value)",
+        "only": args.only, "seeds": {"C2": c2.seed, "C4": c4.seed},
+    }
+
+    # ---- INT8-KV prefill workloads beside the headline (device-seeded N(0,1); a few launches each)
+    if args.only == "all" and not args.no_extras:
+        extras = []
+        for name, iters in (("C3", 10), ("C5", 3)):
+            w = WORKLOADS[name]
+            g = torch.Generator(device="cuda")
+            g.manual_seed(w.seed)
+            qx = torch.randn((w.batch, w.q_heads, w.seq_len, w.head_dim), generator=g, device="cuda",
+                             dtype=torch.float32).to(torch.bfloat16)
+            kx = torch.randn((w.batch, w.kv_heads, w.seq_len, w.head_dim), generator=g, device="cuda",
+                             dtype=torch.float32).to(torch.bfloat16)
+            vx = torch.randn((w.batch, w.kv_heads, w.seq_len, w.head_dim), generator=g, device="cuda",
+                             dtype=torch.float32).to(torch.bfloat16)
+            kcx, ksx = sa.kv_quant_int8(kx)
+            vcx, vsx = sa.kv_quant_int8(vx)
+            ox = torch.empty_like(qx)
+            for _ in range(2):
+                sa.slim_attn_prefill(qx, kcx, vcx, w.softmax_scale, True, k_scale=ksx, v_scale=vsx, out=ox)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(iters):
+                sa.slim_attn_prefill(qx, kcx, vcx, w.softmax_scale, True, k_scale=ksx, v_scale=vsx, out=ox)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / iters
+            fl = acct.prefill_flops(w.batch, w.q_heads, w.seq_len, w.head_dim, True)
+            tf = fl / (ms * 1e-3) / 1e12
+            extras.append({"workload": name + " causal prefill, INT8 K/V", "ms": round(ms, 4), "tflops": round(tf, 2),
+                           "frac_of_bf16_mfma_peak": round(tf / PEAK_BF16_TFLOPS, 4),
+                           "paper_cpu_ms_context": PAPER_TABLE3_MS.get(w.seq_len)})
+            del qx, kx, vx, kcx, vcx, ksx, vsx, ox
+        line["other_workloads"] = extras
+
+    # ---- the CPU oracle on this host's cores, beside the GPU number (a baseline, not a target)
+    if not args.no_cpu_baseline and do_prefill:
+        import oracle
+        n_heads = 8                                   # a bounded sample: 8 of the 32 heads, every row
+        t0 = time.perf_counter()
+        oracle.attn(q2h[:, :n_heads], k2h[:, :n_heads], v2h[:, :n_heads], c2.softmax_scale, True)
+        dt = time.perf_counter() - t0
+        fl = acct.prefill_flops(c2.batch, n_heads, c2.seq_len, c2.head_dim, True)
+        line["cpu_baseline"] = {"value": round(fl / dt / 1e12, 5), "unit": "TFLOP/s", "cores": oracle.num_threads(),
+                                "kind": "oracle", "seconds": round(dt, 3),
+                                "sample": "heads 0-7 of the 32 heads of C2, all 2048 rows (fp64 scalar C, OpenMP)"}
+        if do_decode:
+            nb = 2
+            kc, ks, vc, vs = (t[:nb].cpu().numpy() for t in (kc4, ks4, vc4, vs4))
+            t0 = time.perf_counter()
+            oracle.attn(q4h[:nb], kc, vc, c4.softmax_scale, False, k_scale=ks, v_scale=vs)
+            dt = time.perf_counter() - t0
+            by = acct.decode_bytes(nb, c4.q_heads, c4.kv_heads, c4.seq_len, c4.head_dim)
+            line["cpu_baseline_decode"] = {"value": round(by / dt / 1e9, 3), "unit": "GB/s",
+                                           "cores": oracle.num_threads(), "kind": "oracle", "seconds": round(dt, 3),
+                                           "sample": "sequences 0-1 of the 16 of C4, all heads, all 8192 tokens"}
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
