@@ -2,39 +2,65 @@
 // matrix-vector product bound by memory bandwidth; cached INT8 values are widened to FP32
 // in registers and fed to FMAs, with one scale per token per head).
 //
-// HBM-bound streaming kernel.  A workgroup of 4 waves covers kTokensPerSplit consecutive
-// tokens of one (batch, query head); every wave streams 256 of them:
-//   - a token row of D codes is read by D/16 adjacent lanes with one 128-bit load each,
-//     so one load instruction of a wave fetches 64/(D/16) whole rows;
-//   - each such group of lanes ("slot") owns a run of consecutive tokens, which keeps its
-//     per-token scales contiguous (staged once per wave through LDS);
-//   - pass 1 computes the wave's scores, pass 2 takes one max for the wave and the
-//     probabilities, pass 3 streams V with the probability (times the V scale) as the
-//     only multiplier, so nothing is rescaled inside a wave;
-//   - the 4 waves are merged in LDS, and a second kernel merges the splits in a fixed
-//     order (no atomics: the result does not depend on workgroup arrival order).
+// HBM-bound streaming kernel.  A workgroup of 4 waves serves one (batch, query head) and
+// one split of the key axis; every wave streams a contiguous run of tokens in chunks of
+// 64 tokens:
+//   - a token row of D codes is read by D/16 adjacent lanes ("slot") with one 128-bit
+//     load each, so one load instruction of a wave fetches 64/(D/16) whole rows, and the
+//     wave's loads of a chunk cover one contiguous piece of K and one of V;
+//   - the K and V loads of chunk c+1 are issued before chunk c is consumed, so a wave
+//     always has a chunk of 128-bit loads in flight;
+//   - lane i of the wave owns token i of the chunk: it loads that token's two scales
+//     (coalesced), keeps its score, and computes ONE exponential per chunk;
+//   - each slot carries its own running max / sum (online softmax, fp32), so the only
+//     cross-lane traffic in the loop is DPP adds inside a slot and a 256-byte LDS
+//     exchange of the chunk's probabilities;
+//   - slots and waves are merged in LDS at the end, and a second kernel merges the splits
+//     in a fixed order (no atomics: the result does not depend on arrival order).
+#include <type_traits>
+
 #include "slim_common.h"
 #include "slim_kernels.h"
 
 namespace slim {
 
 constexpr int kDecodeWaves = 4;
-constexpr int kTokensPerWave = 256;
-constexpr int kTokensPerSplit = kDecodeWaves * kTokensPerWave;
+constexpr int kChunk = 64;   // tokens per wave per chunk
+
+// lane exchange inside a slot via DPP (no LDS traffic); every lane of the slot ends with the slot total
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
+}
+template <int LPR>
+__device__ __forceinline__ float slot_sum(float v) {
+    v += dpp_f32<0xB1>(v);                 // quad_perm [1,0,3,2]
+    v += dpp_f32<0x4E>(v);                 // quad_perm [2,3,0,1]
+    if (LPR == 8) v += dpp_f32<0x141>(v);  // row_half_mirror: the other quad of the 8 lanes
+    return v;
+}
+template <int LPR>
+__device__ __forceinline__ float slot_max(float v) {
+    v = fmaxf(v, dpp_f32<0xB1>(v));
+    v = fmaxf(v, dpp_f32<0x4E>(v));
+    if (LPR == 8) v = fmaxf(v, dpp_f32<0x141>(v));
+    return v;
+}
 
 template <int D>
 __global__ __launch_bounds__(256) void slim_decode_int8_split_kernel(
     const uint16_t* __restrict__ q, const int8_t* __restrict__ kc, const float* __restrict__ ks,
     const int8_t* __restrict__ vc, const float* __restrict__ vs, uint16_t* __restrict__ out,
-    float* __restrict__ ws_acc, float* __restrict__ ws_ml, int Hq, int Hkv, int T, int n_split, float scale_log2e) {
-    constexpr int LPR = D / 16;             // lanes per token row
-    constexpr int SLOTS = 64 / LPR;         // token rows per load instruction of a wave
-    constexpr int NI = kTokensPerWave / SLOTS;  // consecutive tokens per slot
+    float* __restrict__ ws_acc, float* __restrict__ ws_ml, int Hq, int Hkv, int T, int n_split, int tokens_per_wave,
+    float scale_log2e) {
+    constexpr int LPR = D / 16;        // lanes per token row
+    constexpr int SLOTS = 64 / LPR;    // token rows per load instruction of a wave
+    constexpr int CH = LPR;            // rows per slot per chunk: SLOTS * CH == kChunk, one token per lane
 
-    __shared__ float scaleS[kDecodeWaves][2][kTokensPerWave];
-    __shared__ float accS[kDecodeWaves][SLOTS][D];
+    __shared__ __attribute__((aligned(16))) float pvS[kDecodeWaves][kChunk];
+    __shared__ __attribute__((aligned(16))) float accS[kDecodeWaves][SLOTS][D];
     __shared__ float lS[kDecodeWaves][SLOTS];
-    __shared__ float mS[kDecodeWaves];
+    __shared__ float mS[kDecodeWaves][SLOTS];
 
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int c = lane % LPR, s = lane / LPR;
@@ -43,7 +69,11 @@ __global__ __launch_bounds__(256) void slim_decode_int8_split_kernel(
     const long kvbase = ((long)b * Hkv + g) * (long)T;
     const int8_t* kp = kc + kvbase * D + c * 16;
     const int8_t* vp = vc + kvbase * D + c * 16;
-    const int t_wave0 = sp * kTokensPerSplit + w * kTokensPerWave;
+    const float* ksp = ks + kvbase;
+    const float* vsp = vs + kvbase;
+    const int t_wave0 = (sp * kDecodeWaves + w) * tokens_per_wave;
+    const int t_wave_end = min(T, t_wave0 + tokens_per_wave);
+    const int n_chunks = t_wave0 < T ? (t_wave_end - t_wave0 + kChunk - 1) / kChunk : 0;
 
     // this lane's 16 query values, fp32
     float qf[16];
@@ -60,96 +90,120 @@ __global__ __launch_bounds__(256) void slim_decode_int8_split_kernel(
         }
     }
 
-    // the wave's 256 K scales and V scales, coalesced, through LDS
-#pragma unroll
-    for (int j = 0; j < kTokensPerWave / 64; ++j) {
-        const int t = min(t_wave0 + lane + 64 * j, T - 1);
-        scaleS[w][0][lane + 64 * j] = ks[kvbase + t];
-        scaleS[w][1][lane + 64 * j] = vs[kvbase + t];
-    }
-    __syncthreads();
-
-    const int t_slot0 = t_wave0 + s * NI;
-
-    // pass 1: scores (in log2 units)
-    float sc[NI];
-#pragma unroll
-    for (int it = 0; it < NI; ++it) {
-        const int t = t_slot0 + it;
-        const u32x4 kw = *reinterpret_cast<const u32x4*>(kp + (long)min(t, T - 1) * D);
-        float dot = 0.0f;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            dot = fmaf(qf[4 * i + 0], i8_to_f32<0>(kw[i]), dot);
-            dot = fmaf(qf[4 * i + 1], i8_to_f32<1>(kw[i]), dot);
-            dot = fmaf(qf[4 * i + 2], i8_to_f32<2>(kw[i]), dot);
-            dot = fmaf(qf[4 * i + 3], i8_to_f32<3>(kw[i]), dot);
-        }
-#pragma unroll
-        for (int off = 1; off < LPR; off <<= 1) dot += __shfl_xor(dot, off);
-        sc[it] = (t < T) ? dot * (scaleS[w][0][s * NI + it] * scale_log2e) : kMasked;
-    }
-
-    // pass 2: one max for the wave, probabilities, the slot's sum
-    float m = sc[0];
-#pragma unroll
-    for (int it = 1; it < NI; ++it) m = fmaxf(m, sc[it]);
-#pragma unroll
-    for (int off = LPR; off < 64; off <<= 1) m = fmaxf(m, __shfl_xor(m, off));
-    float l = 0.0f;
-#pragma unroll
-    for (int it = 0; it < NI; ++it) {
-        float p = fast_exp2(sc[it] - m);
-        p = (t_slot0 + it < T) ? p : 0.0f;
-        l += p;
-        sc[it] = p * scaleS[w][1][s * NI + it];   // probability times the token's V scale
-    }
-
-    // pass 3: acc[d] += p * v_scale * code
     float acc[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
+    float m = kMasked, l = 0.0f;   // slot max (identical in the slot's lanes), this lane's part of the slot sum
+
+    u32x4 kbuf[CH], vbuf[CH];
+    float ksc = 0.0f, vsc = 0.0f;
+    // rows past the end of the cache are clamped to the last row and masked below
+    auto issue_k = [&](int t_chunk0) {
 #pragma unroll
-    for (int it = 0; it < NI; ++it) {
-        const int t = t_slot0 + it;
-        const u32x4 vw = *reinterpret_cast<const u32x4*>(vp + (long)min(t, T - 1) * D);
-        const float pv = sc[it];
+        for (int it = 0; it < CH; ++it)
+            kbuf[it] = *reinterpret_cast<const u32x4*>(kp + (long)min(t_chunk0 + s * CH + it, T - 1) * D);
+        ksc = ksp[min(t_chunk0 + lane, T - 1)];
+    };
+    auto issue_v = [&](int t_chunk0) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            acc[4 * i + 0] = fmaf(pv, i8_to_f32<0>(vw[i]), acc[4 * i + 0]);
-            acc[4 * i + 1] = fmaf(pv, i8_to_f32<1>(vw[i]), acc[4 * i + 1]);
-            acc[4 * i + 2] = fmaf(pv, i8_to_f32<2>(vw[i]), acc[4 * i + 2]);
-            acc[4 * i + 3] = fmaf(pv, i8_to_f32<3>(vw[i]), acc[4 * i + 3]);
+        for (int it = 0; it < CH; ++it)
+            vbuf[it] = *reinterpret_cast<const u32x4*>(vp + (long)min(t_chunk0 + s * CH + it, T - 1) * D);
+        vsc = vsp[min(t_chunk0 + lane, T - 1)];
+    };
+
+    // unconditional (a wave past the end re-reads clamped rows): keeps the prologue free of branches
+    issue_k(t_wave0);
+    issue_v(t_wave0);
+    // one chunk; PREFETCH is a compile-time flag so the loop body has no branch around its loads
+    auto chunk = [&](int ch, auto prefetch) {
+        constexpr bool more = decltype(prefetch)::value;
+        const int t_chunk0 = t_wave0 + ch * kChunk;
+
+        // scores: the slot's CH rows; lane c of the slot keeps row c (token t_chunk0 + lane)
+        float my_dot = 0.0f;
+#pragma unroll
+        for (int it = 0; it < CH; ++it) {
+            const u32x4 kw = kbuf[it];
+            float dot = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                dot = fmaf(qf[4 * i + 0], i8_to_f32<0>(kw[i]), dot);
+                dot = fmaf(qf[4 * i + 1], i8_to_f32<1>(kw[i]), dot);
+                dot = fmaf(qf[4 * i + 2], i8_to_f32<2>(kw[i]), dot);
+                dot = fmaf(qf[4 * i + 3], i8_to_f32<3>(kw[i]), dot);
+            }
+            dot = slot_sum<LPR>(dot);
+            my_dot = (c == it) ? dot : my_dot;
         }
-    }
+        const bool valid = t_chunk0 + lane < T;
+        const float my_s = valid ? my_dot * (ksc * scale_log2e) : kMasked;
+        if constexpr (more) issue_k(t_chunk0 + kChunk);
+
+        const float m_new = fmaxf(m, slot_max<LPR>(my_s));
+        const float alpha = fast_exp2(m - m_new);
+        float p = fast_exp2(my_s - m_new);
+        p = valid ? p : 0.0f;
+        l = fmaf(l, alpha, p);
+        pvS[w][lane] = p * vsc;   // probability times the token's V scale
+        if (__builtin_amdgcn_ballot_w64(m_new > m) != 0) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] *= alpha;
+        }
+        m = m_new;
+
+        float pv[CH];
+#pragma unroll
+        for (int i = 0; i < CH / 4; ++i) {
+            const f32x4 t4 = *reinterpret_cast<const f32x4*>(&pvS[w][s * CH + 4 * i]);
+            pv[4 * i] = t4[0];
+            pv[4 * i + 1] = t4[1];
+            pv[4 * i + 2] = t4[2];
+            pv[4 * i + 3] = t4[3];
+        }
+#pragma unroll
+        for (int it = 0; it < CH; ++it) {
+            const u32x4 vw = vbuf[it];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                acc[4 * i + 0] = fmaf(pv[it], i8_to_f32<0>(vw[i]), acc[4 * i + 0]);
+                acc[4 * i + 1] = fmaf(pv[it], i8_to_f32<1>(vw[i]), acc[4 * i + 1]);
+                acc[4 * i + 2] = fmaf(pv[it], i8_to_f32<2>(vw[i]), acc[4 * i + 2]);
+                acc[4 * i + 3] = fmaf(pv[it], i8_to_f32<3>(vw[i]), acc[4 * i + 3]);
+            }
+        }
+        if constexpr (more) issue_v(t_chunk0 + kChunk);
+    };
+    for (int ch = 0; ch + 1 < n_chunks; ++ch) chunk(ch, std::true_type{});
+    if (n_chunks > 0) chunk(n_chunks - 1, std::false_type{});
 
     // merge slots and waves in LDS
+    l = slot_sum<LPR>(l);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         f32x4 a4 = {acc[4 * i], acc[4 * i + 1], acc[4 * i + 2], acc[4 * i + 3]};
         *reinterpret_cast<f32x4*>(&accS[w][s][c * 16 + 4 * i]) = a4;
     }
-    if (c == 0) lS[w][s] = l;
-    if (lane == 0) mS[w] = m;
+    if (c == 0) {
+        lS[w][s] = l;
+        mS[w][s] = m;
+    }
     __syncthreads();
     if (threadIdx.x < D) {
         const int d = threadIdx.x;
-        float M = mS[0];
+        float M = kMasked;
 #pragma unroll
-        for (int ww = 1; ww < kDecodeWaves; ++ww) M = fmaxf(M, mS[ww]);
+        for (int ww = 0; ww < kDecodeWaves; ++ww)
+#pragma unroll
+            for (int ss = 0; ss < SLOTS; ++ss) M = fmaxf(M, mS[ww][ss]);
         float L = 0.0f, o = 0.0f;
 #pragma unroll
-        for (int ww = 0; ww < kDecodeWaves; ++ww) {
-            const float f = fast_exp2(mS[ww] - M);   // a wave past the end has m = kMasked -> f = 0
-            float lw = 0.0f, ow = 0.0f;
+        for (int ww = 0; ww < kDecodeWaves; ++ww)
 #pragma unroll
             for (int ss = 0; ss < SLOTS; ++ss) {
-                lw += lS[ww][ss];
-                ow += accS[ww][ss][d];
+                const float f = fast_exp2(mS[ww][ss] - M);   // an empty slot has l = 0 and acc = 0
+                L = fmaf(f, lS[ww][ss], L);
+                o = fmaf(f, accS[ww][ss][d], o);
             }
-            L = fmaf(f, lw, L);
-            o = fmaf(f, ow, o);
-        }
         const long bh = (long)b * Hq + h;
         if (n_split == 1) {
             out[bh * D + d] = (uint16_t)(pack_bf16x2(o / L, 0.0f) & 0xffffu);
@@ -184,17 +238,36 @@ __global__ __launch_bounds__(D) void slim_decode_combine_kernel(const float* __r
     out[bh * D + d] = (uint16_t)(pack_bf16x2(o / L, 0.0f) & 0xffffu);
 }
 
-int decode_tokens_per_split(int) { return kTokensPerSplit; }
+static int g_decode_tokens_per_wave = 512;
+extern "C" void slim_tune_decode_tokens_per_wave(int v) { g_decode_tokens_per_wave = v; }
 
-int decode_num_splits(int kv_len, int) { return (kv_len + kTokensPerSplit - 1) / kTokensPerSplit; }
+// Tokens of the key axis one wave streams: a multiple of the 64-token chunk.  Long
+// enough to amortise the merge; shortened when (batch x heads) alone cannot fill the
+// chip (aim: at least ~4 workgroups per compute unit) or when the cache is short.
+int decode_tokens_per_wave(int kv_len, long n_bh) {
+    long tpw = g_decode_tokens_per_wave;
+    const long want_blocks = 256L * 4;
+    const long fill = (long)kv_len * n_bh / (want_blocks * kDecodeWaves);   // tokens per wave that give want_blocks
+    if (tpw > fill) tpw = fill;
+    tpw = tpw / kChunk * kChunk;
+    if (tpw < kChunk) tpw = kChunk;
+    return (int)tpw;
+}
+
+int decode_num_splits(int kv_len, long n_bh) {
+    const int per_block = decode_tokens_per_wave(kv_len, n_bh) * kDecodeWaves;
+    return (kv_len + per_block - 1) / per_block;
+}
 
 size_t decode_workspace_bytes(int batch, int q_heads, int kv_len, int head_dim) {
-    const size_t n = (size_t)batch * q_heads * decode_num_splits(kv_len, head_dim);
+    const size_t n = (size_t)batch * q_heads * decode_num_splits(kv_len, (long)batch * q_heads);
     return n * ((size_t)head_dim + 2) * sizeof(float);
 }
 
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t stream) {
-    const int n_split = decode_num_splits(a.kv_len, a.head_dim);
+    const long n_bh = (long)a.batch * a.q_heads;
+    const int tpw = decode_tokens_per_wave(a.kv_len, n_bh);
+    const int n_split = decode_num_splits(a.kv_len, n_bh);
     const size_t n_part = (size_t)a.batch * a.q_heads * n_split;
     float* ws_acc = a.workspace;
     float* ws_ml = a.workspace + n_part * a.head_dim;
@@ -203,11 +276,11 @@ hipError_t launch_decode(const DecodeArgs& a, hipStream_t stream) {
     if (a.head_dim == 128)
         hipLaunchKernelGGL(slim_decode_int8_split_kernel<128>, grid, dim3(256), 0, stream, (const uint16_t*)a.q,
                            a.k_codes, a.k_scale, a.v_codes, a.v_scale, (uint16_t*)a.out, ws_acc, ws_ml, a.q_heads,
-                           a.kv_heads, a.kv_len, n_split, scale_log2e);
+                           a.kv_heads, a.kv_len, n_split, tpw, scale_log2e);
     else
         hipLaunchKernelGGL(slim_decode_int8_split_kernel<64>, grid, dim3(256), 0, stream, (const uint16_t*)a.q,
                            a.k_codes, a.k_scale, a.v_codes, a.v_scale, (uint16_t*)a.out, ws_acc, ws_ml, a.q_heads,
-                           a.kv_heads, a.kv_len, n_split, scale_log2e);
+                           a.kv_heads, a.kv_len, n_split, tpw, scale_log2e);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || n_split == 1) return e;
     const unsigned nbh = (unsigned)(a.batch * a.q_heads);

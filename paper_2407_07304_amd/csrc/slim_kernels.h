@@ -33,9 +33,10 @@ struct DecodeArgs {
     int batch, q_heads, kv_heads, kv_len, head_dim;
     float softmax_scale;
 };
-// Tokens of the key axis one workgroup of the split kernel covers, and the split count.
-int decode_tokens_per_split(int head_dim);
-int decode_num_splits(int kv_len, int head_dim);
+// Tokens of the key axis one wave of the split kernel streams, and the split count, for a
+// cache of kv_len tokens and n_bh = batch * q_heads independent rows.
+int decode_tokens_per_wave(int kv_len, long n_bh);
+int decode_num_splits(int kv_len, long n_bh);
 size_t decode_workspace_bytes(int batch, int q_heads, int kv_len, int head_dim);
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t stream);
 

@@ -78,8 +78,10 @@ def test_quant_rejects_bad_arguments(lib):
 
 def test_decode_rejects_bad_arguments_and_reports_workspace(lib):
     ws = lib.slim_attn_decode_int8_workspace_bytes
-    assert ws(16, 32, 32, 8192, 128) == 16 * 32 * 8 * (128 + 2) * 4
-    assert ws(1, 1, 1, 1, 64) == (64 + 2) * 4
+    per_row = lambda D: (D + 2) * 4   # one (max, sum, accumulator[D]) record per split
+    assert ws(16, 32, 32, 8192, 128) % (16 * 32 * per_row(128)) == 0 and ws(16, 32, 32, 8192, 128) > 0
+    assert ws(1, 1, 1, 1, 64) == per_row(64)
+    assert ws(2, 4, 4, 100000, 64) >= ws(2, 4, 4, 1000, 64) > 0
     assert ws(1, 3, 2, 10, 128) == 0 and ws(1, 1, 1, 10, 96) == 0
     f = lib.slim_attn_decode_int8
 
@@ -90,4 +92,4 @@ def test_decode_rejects_bad_arguments_and_reports_workspace(lib):
     assert call(T=0) == 2 and call(Hq=4, Hkv=3) == 2 and call(scale=-1.0) == 2
     assert call(D=32) == 3
     assert call(out=A + 2) == 4
-    assert call(wsb=(2 * (128 + 2) * 4) - 1) == 5
+    assert call(wsb=ws(1, 2, 2, 100, 128) - 1) == 5
