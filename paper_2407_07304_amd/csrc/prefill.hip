@@ -20,6 +20,8 @@
 //   - Software pipeline: the score MFMAs of step k+1 are issued before the softmax of
 //     step k, so the matrix pipe works while the vector ALU does the exponentials; a
 //     three-deep LDS ring is filled through registers one step ahead, one barrier per step.
+#include <type_traits>
+
 #include "slim_common.h"
 #include "slim_kernels.h"
 
@@ -61,7 +63,7 @@ __device__ __forceinline__ float half_sum(float x) {
 }
 
 template <int D, bool KV_I8, bool OUT_F32>
-__global__ __launch_bounds__(kPrefillThreads, 2) void slim_prefill_kernel(const PrefillParams p) {
+__global__ __launch_bounds__(kPrefillThreads, 1) void slim_prefill_kernel(const PrefillParams p) {
     constexpr int KS = D / 16;       // k-steps of the score MFMA
     constexpr int DT = D / 32;       // 32-row tiles of O^T
     constexpr int LDKK = D + 8;      // K rows: 16 B of padding, conflict-free 128-bit row reads
@@ -90,28 +92,38 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void slim_prefill_kernel(const 
     const long kvrow0 = ((long)b * p.Hkv + g) * (long)S;
 
     // ---- staging: global -> registers (one step ahead) -> LDS ring
+    // Addresses: a uniform base (this head's K / V slab) plus a 32-bit per-thread offset, so the loads
+    // take the scalar-base form; the LDS destinations are a per-thread constant plus the ring slot.
+    constexpr int ROWB = KV_I8 ? D : 2 * D;   // bytes per K/V row in memory
+    const char* kslab = (const char*)p.k + kvrow0 * ROWB;
+    const char* vslab = (const char*)p.v + kvrow0 * ROWB;
+    const float* ksslab = KV_I8 ? p.ks + kvrow0 : nullptr;
+    const float* vsslab = KV_I8 ? p.vs + kvrow0 : nullptr;
+    int st_row[NCH], st_colb[NCH], st_kdst[NCH], st_vdst[NCH];
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+        const int cidx = tid + kPrefillThreads * i;
+        st_row[i] = cidx / CPR;
+        st_colb[i] = (cidx % CPR) * 16;
+        st_kdst[i] = st_row[i] * LDKK + (cidx % CPR) * (KV_I8 ? 16 : 8);
+        st_vdst[i] = st_row[i] * LDKV + (cidx % CPR) * (KV_I8 ? 16 : 8);
+    }
     u32x4 kst[NCH], vst[NCH];
     float sst = 0.0f;
     auto load_step = [&](int s) {
         const int j0 = s * kBC;
 #pragma unroll
         for (int i = 0; i < NCH; ++i) {
-            const int cidx = tid + kPrefillThreads * i;
-            if (NCHUNK % kPrefillThreads == 0 || cidx < NCHUNK) {
-                const int row = cidx / CPR, col = cidx % CPR;
-                const long grow = kvrow0 + min(j0 + row, S - 1);   // rows past the end: clamped, masked later
-                if (KV_I8) {
-                    kst[i] = *reinterpret_cast<const u32x4*>((const int8_t*)p.k + grow * D + col * 16);
-                    vst[i] = *reinterpret_cast<const u32x4*>((const int8_t*)p.v + grow * D + col * 16);
-                } else {
-                    kst[i] = *reinterpret_cast<const u32x4*>((const uint16_t*)p.k + grow * D + col * 8);
-                    vst[i] = *reinterpret_cast<const u32x4*>((const uint16_t*)p.v + grow * D + col * 8);
-                }
+            if (NCHUNK % kPrefillThreads == 0 || tid + kPrefillThreads * i < NCHUNK) {
+                // rows past the end of the sequence: clamped here, masked in the softmax
+                const unsigned off = (unsigned)min(j0 + st_row[i], S - 1) * (unsigned)ROWB + (unsigned)st_colb[i];
+                kst[i] = *reinterpret_cast<const u32x4*>(kslab + off);
+                vst[i] = *reinterpret_cast<const u32x4*>(vslab + off);
             }
         }
         if (KV_I8) {
-            if (tid < kBC) sst = p.ks[kvrow0 + min(j0 + tid, S - 1)];
-            else if (tid < 2 * kBC) sst = p.vs[kvrow0 + min(j0 + tid - kBC, S - 1)];
+            if (tid < kBC) sst = ksslab[min(j0 + tid, S - 1)];
+            else if (tid < 2 * kBC) sst = vsslab[min(j0 + tid - kBC, S - 1)];
         }
     };
     auto widen16 = [&](const u32x4 cw, uint16_t* dst) {   // 16 INT8 codes -> 16 bf16 (exact)
@@ -127,17 +139,17 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void slim_prefill_kernel(const 
         *reinterpret_cast<u32x4*>(dst + 8) = hi;
     };
     auto store_step = [&](int buf) {
+        uint16_t* kdst = &Ks[0][0] + buf * (kBC * LDKK);
+        uint16_t* vdst = &Vs[0][0] + buf * (kBC * LDKV);
 #pragma unroll
         for (int i = 0; i < NCH; ++i) {
-            const int cidx = tid + kPrefillThreads * i;
-            if (NCHUNK % kPrefillThreads == 0 || cidx < NCHUNK) {
-                const int row = cidx / CPR, col = cidx % CPR;
+            if (NCHUNK % kPrefillThreads == 0 || tid + kPrefillThreads * i < NCHUNK) {
                 if (KV_I8) {
-                    widen16(kst[i], &Ks[buf][row * LDKK + col * 16]);
-                    widen16(vst[i], &Vs[buf][row * LDKV + col * 16]);
+                    widen16(kst[i], kdst + st_kdst[i]);
+                    widen16(vst[i], vdst + st_vdst[i]);
                 } else {
-                    *reinterpret_cast<u32x4*>(&Ks[buf][row * LDKK + col * 8]) = kst[i];
-                    *reinterpret_cast<u32x4*>(&Vs[buf][row * LDKV + col * 8]) = vst[i];
+                    *reinterpret_cast<u32x4*>(kdst + st_kdst[i]) = kst[i];
+                    *reinterpret_cast<u32x4*>(vdst + st_vdst[i]) = vst[i];
                 }
             }
         }
@@ -149,13 +161,15 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void slim_prefill_kernel(const 
 
     bf16x8 qreg[KS];
     f32x16 o[DT];
+    const int ka_off = l32 * LDKK + 8 * hh;                                              // K fragment (row l32)
+    const int va_off = (4 * hh + (l & 15) / 4) * LDKV + 16 * ((l >> 4) & 1) + 4 * (l & 3);   // V transpose read
 
     // S^T[key][query] = sum_d K[key][d] Q[query][d] for the 32 keys of a step
     auto score = [&](int buf) {
         f32x16 st;
 #pragma unroll
         for (int r = 0; r < 16; ++r) st[r] = 0.0f;
-        const uint16_t* ka = &Ks[buf][l32 * LDKK + 8 * hh];
+        const uint16_t* ka = &Ks[0][0] + buf * (kBC * LDKK) + ka_off;
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
             const bf16x8 a = *reinterpret_cast<const bf16x8*>(ka + 16 * s);
@@ -175,7 +189,6 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void slim_prefill_kernel(const 
         // last step this wave computes: its diagonal step under the causal mask; none if it has no row
         const int wave_last = wave_q_lo >= S ? -1 : (p.causal ? min(n_steps - 1, wave_q_lo / kBC) : n_steps - 1);
         const int lim = p.causal ? min(my_q, S - 1) : S - 1;   // last key this lane's row may see
-        const int wave_lim_min = p.causal ? min(wave_q_lo, S - 1) : S - 1;   // the smallest such limit in the wave
 
         // Q^T B-operands: lane holds row my_q, d = 16 s + 8 hh + [0,8)
         {
@@ -197,105 +210,220 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void slim_prefill_kernel(const 
         store_step(1);
         load_step(min(2, n_steps - 1));
         __syncthreads();
-        f32x16 st_next;
+        // Steady-state step k of this wave (k is below its diagonal, no mask).  The instruction order is
+        // fixed by hand (sched_barrier) for a wave that runs alone on its SIMD:
+        //   K fragments of step k+1  ->  row max / alpha of step k  ->  score MFMAs of step k+1, each
+        //   followed by a slice of step k's exponentials  ->  ring traffic  ->  P V MFMAs of step k with
+        //   the V fragment reads between them.
+        auto steady_step = [&](int k, int buf, f32x16& st_cur, f32x16& st_nxt) {
+            constexpr int EPM = 16 / KS;   // exponentials issued after each score MFMA
+            const int nbuf = buf == kNS - 1 ? 0 : buf + 1;
+            const int wbuf = nbuf == kNS - 1 ? 0 : nbuf + 1;
+            bf16x8 kfr[KS];
+            {
+                const uint16_t* ka = &Ks[0][0] + nbuf * (kBC * LDKK) + ka_off;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) st_next[r] = 0.0f;
-        if (wave_last >= 0) st_next = score(0);
-
-        for (int k = 0; k < n_steps; ++k) {
-            const int buf = k % kNS;
-            const bool active = k <= wave_last;          // wave-uniform
-            f32x16 st = st_next;
-            if (k + 1 <= wave_last) st_next = score((k + 1) % kNS);
-
-            u32x4 pw[2];
-            if (active) {
-                const int key0 = k * kBC;
-                // register r of this lane is key  key0 + 8 (r/4) + 4 hh + r%4
-                float t[16];
-                if (KV_I8) {
-#pragma unroll
-                    for (int r4 = 0; r4 < 4; ++r4) {
-                        const f32x4 kf = *reinterpret_cast<const f32x4*>(&scS[buf][8 * r4 + 4 * hh]);
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) t[4 * r4 + e] = st[4 * r4 + e] * kf[e];
-                    }
-                } else {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) t[r] = st[r];
-                }
-                if (key0 + kBC - 1 > wave_lim_min) {   // diagonal or tail step (wave-uniform)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int key = key0 + 8 * (r / 4) + 4 * hh + (r % 4);
-                        t[r] = (key <= lim) ? t[r] : kMasked;
-                    }
-                }
-                float mloc = fmaxf(t[0], t[1]);
-#pragma unroll
-                for (int r = 2; r < 16; r += 2) mloc = fmaxf(mloc, fmaxf(t[r], t[r + 1]));
-                const float m_new = fmaxf(m, half_max(mloc));
-                float alpha, mc;
-                if (KV_I8) {
-                    alpha = fast_exp2(m - m_new);
-                    mc = m_new;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) t[r] = fast_exp2(t[r] - mc);
-                } else {
-                    alpha = fast_exp2((m - m_new) * c);
-                    mc = m_new * c;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) t[r] = fast_exp2(fmaf(t[r], c, -mc));
-                }
-                float ps = 0.0f;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) ps += t[r];
-                lsum = fmaf(lsum, alpha, ps);
-                if (KV_I8) {
-                    // the probabilities take their token's v_scale before they are rounded to bf16
-#pragma unroll
-                    for (int r4 = 0; r4 < 4; ++r4) {
-                        const f32x4 vf = *reinterpret_cast<const f32x4*>(&scS[buf][kBC + 8 * r4 + 4 * hh]);
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) t[4 * r4 + e] *= vf[e];
-                    }
-                }
-#pragma unroll
-                for (int u = 0; u < 2; ++u)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) pw[u][i] = pack_bf16x2(t[8 * u + 2 * i], t[8 * u + 2 * i + 1]);
-                if (__builtin_amdgcn_ballot_w64(m_new > m) != 0) {   // rescale only when some row's max moved
-#pragma unroll
-                    for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
-                }
-                m = m_new;
+                for (int s = 0; s < KS; ++s) kfr[s] = *reinterpret_cast<const bf16x8*>(ka + 16 * s);
             }
-
-            // ring: registers (step k+2) -> LDS, then fetch step k+3 into registers
-            store_step((k + 2) % kNS);
-            load_step(min(k + 3, n_steps - 1));
-
-            if (active) {
-                // O^T[d][query] += sum_key V[key][d] P[query][key]; k-step u covers registers 8u..8u+7,
-                // i.e. keys 16u + {4hh..4hh+3} and 16u + 8 + {4hh..4hh+3} of the step
+            float t[16];
+            if (KV_I8) {
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    const bf16x8 pb = __builtin_bit_cast(bf16x8, pw[u]);
-                    // transpose read: the 16 lanes of a group fetch rows k..k+3 (4 lanes per row, 4 columns
-                    // each) and lane i of the group receives column i of those 4 rows
-                    const uint16_t* va = &Vs[buf][(16 * u + 4 * hh + (l & 15) / 4) * LDKV + 16 * ((l >> 4) & 1) + 4 * (l & 3)];
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const f32x4 kf = *reinterpret_cast<const f32x4*>(&scS[buf][8 * r4 + 4 * hh]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) t[4 * r4 + e] = st_cur[4 * r4 + e] * kf[e];
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) t[r] = st_cur[r];
+            }
+            float mloc = fmaxf(t[0], t[1]);
+#pragma unroll
+            for (int r = 2; r < 16; r += 2) mloc = fmaxf(mloc, fmaxf(t[r], t[r + 1]));
+            const float m_new = fmaxf(m, half_max(mloc));
+            const float alpha = KV_I8 ? fast_exp2(m - m_new) : fast_exp2((m - m_new) * c);
+            const float mc = KV_I8 ? m_new : m_new * c;
+            if (__builtin_amdgcn_ballot_w64(m_new > m) != 0) {   // rescale only when some row's max moved
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+            }
+            m = m_new;
+            __builtin_amdgcn_sched_barrier(0);
+
+            const uint16_t* va = &Vs[0][0] + buf * (kBC * LDKV) + va_off;
+            s16x4 vlo[DT], vhi[DT];
+            float ps = 0.0f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) st_nxt[r] = 0.0f;
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                st_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[s], qreg[s], st_nxt, 0, 0, 0);
+#pragma unroll
+                for (int e = s * EPM; e < (s + 1) * EPM; ++e) {
+                    t[e] = KV_I8 ? fast_exp2(t[e] - mc) : fast_exp2(fmaf(t[e], c, -mc));
+                    ps += t[e];
+                }
+                if (s == KS / 2) {   // V fragments of the first 16 keys, in flight under the remaining exponentials
 #pragma unroll
                     for (int dt = 0; dt < DT; ++dt) {
-                        const s16x4 lo = lds_read_tr16(va + 32 * dt);
-                        const s16x4 hi = lds_read_tr16(va + 8 * LDKV + 32 * dt);
-                        const s16x8 av = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                        o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb, o[dt], 0, 0, 0);
+                        vlo[dt] = lds_read_tr16(va + 32 * dt);
+                        vhi[dt] = lds_read_tr16(va + 8 * LDKV + 32 * dt);
                     }
+                }
+            }
+            lsum = fmaf(lsum, alpha, ps);
+            if (KV_I8) {
+                // the probabilities take their token's v_scale before they are rounded to bf16
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const f32x4 vf = *reinterpret_cast<const f32x4*>(&scS[buf][kBC + 8 * r4 + 4 * hh]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) t[4 * r4 + e] *= vf[e];
+                }
+            }
+            u32x4 pw[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) pw[u][i] = pack_bf16x2(t[8 * u + 2 * i], t[8 * u + 2 * i + 1]);
+            // ring: registers (step k+2) -> LDS, then fetch step k+3 into registers
+            store_step(wbuf);
+            load_step(min(k + 3, n_steps - 1));
+
+            // O^T[d][query] += sum_key V[key][d] P[query][key]; k-step u covers registers 8u..8u+7,
+            // i.e. keys 16u + {4hh..4hh+3} and 16u + 8 + {4hh..4hh+3} of the step
+            s16x4 wlo[DT], whi[DT];
+            const bf16x8 pb0 = __builtin_bit_cast(bf16x8, pw[0]);
+            const bf16x8 pb1 = __builtin_bit_cast(bf16x8, pw[1]);
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                wlo[dt] = lds_read_tr16(va + 16 * LDKV + 32 * dt);
+                whi[dt] = lds_read_tr16(va + 24 * LDKV + 32 * dt);
+                const s16x8 av = {vlo[dt][0], vlo[dt][1], vlo[dt][2], vlo[dt][3], vhi[dt][0], vhi[dt][1], vhi[dt][2], vhi[dt][3]};
+                o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb0, o[dt], 0, 0, 0);
+            }
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                const s16x8 av = {wlo[dt][0], wlo[dt][1], wlo[dt][2], wlo[dt][3], whi[dt][0], whi[dt][1], whi[dt][2], whi[dt][3]};
+                o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb1, o[dt], 0, 0, 0);
+            }
+            // instruction pipeline of the region above (one scheduling region): every score MFMA is followed
+            // by a slice of the exponentials, the ring traffic sits between the two MFMA runs, and the
+            // second half of the V fragments is read under the first P V MFMAs
+#pragma unroll
+            for (int s = 0; s < KS; ++s) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                 // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x002, (KV_I8 ? 4 : 3) * EPM + 1, 0);   // its share of the softmax VALU work
+                if (s == KS / 2) __builtin_amdgcn_sched_group_barrier(0x100, 2 * DT, 0);   // V fragments, first 16 keys
+            }
+            __builtin_amdgcn_sched_group_barrier(0x002, 16, 0);    // row sum, packing
+            __builtin_amdgcn_sched_group_barrier(0x200, 2 * NCH * (KV_I8 ? 2 : 1), 0);   // ring: LDS writes
+            __builtin_amdgcn_sched_group_barrier(0x020, 2 * NCH, 0);                       // ring: global loads
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, DT, 0);
+            __syncthreads();
+        };
+        // The wave's last step (its diagonal under the causal mask, or the tail of the key axis): masked,
+        // nothing to issue ahead.
+        auto last_step = [&](int k, int buf, f32x16& st_cur) {
+            const int wbuf = buf == 0 ? kNS - 1 : buf - 1;   // (buf + 2) mod 3
+            const int key0 = k * kBC;
+            // register r of this lane is key  key0 + 8 (r/4) + 4 hh + r%4
+            float t[16];
+            if (KV_I8) {
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const f32x4 kf = *reinterpret_cast<const f32x4*>(&scS[buf][8 * r4 + 4 * hh]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) t[4 * r4 + e] = st_cur[4 * r4 + e] * kf[e];
+                }
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) t[r] = st_cur[r];
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = key0 + 8 * (r / 4) + 4 * hh + (r % 4);
+                t[r] = (key <= lim) ? t[r] : kMasked;
+            }
+            float mloc = fmaxf(t[0], t[1]);
+#pragma unroll
+            for (int r = 2; r < 16; r += 2) mloc = fmaxf(mloc, fmaxf(t[r], t[r + 1]));
+            const float m_new = fmaxf(m, half_max(mloc));
+            const float alpha = KV_I8 ? fast_exp2(m - m_new) : fast_exp2((m - m_new) * c);
+            const float mc = KV_I8 ? m_new : m_new * c;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+            m = m_new;
+            float ps = 0.0f;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                t[r] = KV_I8 ? fast_exp2(t[r] - mc) : fast_exp2(fmaf(t[r], c, -mc));
+                ps += t[r];
+            }
+            lsum = fmaf(lsum, alpha, ps);
+            if (KV_I8) {
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const f32x4 vf = *reinterpret_cast<const f32x4*>(&scS[buf][kBC + 8 * r4 + 4 * hh]);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) t[4 * r4 + e] *= vf[e];
+                }
+            }
+            u32x4 pw[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) pw[u][i] = pack_bf16x2(t[8 * u + 2 * i], t[8 * u + 2 * i + 1]);
+            store_step(wbuf);
+            load_step(min(k + 3, n_steps - 1));
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const bf16x8 pb = __builtin_bit_cast(bf16x8, pw[u]);
+                // transpose read: the 16 lanes of a group fetch rows k..k+3 (4 lanes per row, 4 columns
+                // each) and lane i of the group receives column i of those 4 rows
+                const uint16_t* va = &Vs[0][0] + buf * (kBC * LDKV) + va_off + 16 * u * LDKV;
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    const s16x4 lo = lds_read_tr16(va + 32 * dt);
+                    const s16x4 hi = lds_read_tr16(va + 8 * LDKV + 32 * dt);
+                    const s16x8 av = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb, o[dt], 0, 0, 0);
                 }
             }
             __syncthreads();
+        };
+        // one step for this wave, whatever its role in it
+        auto do_step = [&](int k, int buf, f32x16& st_cur, f32x16& st_nxt) {
+            if (k < wave_last) {
+                steady_step(k, buf, st_cur, st_nxt);
+            } else if (k == wave_last) {
+                last_step(k, buf, st_cur);
+            } else {   // past this wave's diagonal: keep the ring and the barriers going
+                store_step(buf == 0 ? kNS - 1 : buf - 1);
+                load_step(min(k + 3, n_steps - 1));
+                __syncthreads();
+            }
+        };
+
+        f32x16 st_a, st_b;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) st_a[r] = st_b[r] = 0.0f;
+        if (wave_last >= 0) st_a = score(0);
+        int buf = 0;
+        for (int k = 0; k < n_steps; k += 2) {
+            do_step(k, buf, st_a, st_b);
+            buf = buf == kNS - 1 ? 0 : buf + 1;
+            if (k + 1 < n_steps) do_step(k + 1, buf, st_b, st_a);
+            buf = buf == kNS - 1 ? 0 : buf + 1;
         }
 
         // epilogue: O = O^T / l ; register r of tile dt is d = 32 dt + 8 (r/4) + 4 hh + r%4
