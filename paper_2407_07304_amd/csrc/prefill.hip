@@ -240,16 +240,20 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void slim_prefill_kernel(const 
             float mloc = fmaxf(t[0], t[1]);
 #pragma unroll
             for (int r = 2; r < 16; r += 2) mloc = fmaxf(mloc, fmaxf(t[r], t[r + 1]));
-            const float m_new = fmaxf(m, half_max(mloc));
-            const float alpha = KV_I8 ? fast_exp2(m - m_new) : fast_exp2((m - m_new) * c);
-            const float mc = KV_I8 ? m_new : m_new * c;
-            if (__builtin_amdgcn_ballot_w64(m_new > m) != 0) {   // rescale only when some row's max moved
+            // lazy running max: it only moves when some row's max grew by more than 2^8, so the
+            // probabilities stay below 256 and the accumulator is rescaled a few times per row block
+            const float cand = fmaxf(m, half_max(mloc));
+            const float jump = KV_I8 ? cand - m : (cand - m) * c;
+            if (__builtin_amdgcn_ballot_w64(jump > 8.0f) != 0) {
+                const float alpha = fast_exp2(KV_I8 ? m - cand : (m - cand) * c);
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+                lsum *= alpha;
+                m = cand;
             }
-            m = m_new;
+            const float mc = KV_I8 ? m : m * c;
             __builtin_amdgcn_sched_barrier(0);
 
             const uint16_t* va = &Vs[0][0] + buf * (kBC * LDKV) + va_off;
@@ -273,7 +277,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void slim_prefill_kernel(const 
                     }
                 }
             }
-            lsum = fmaf(lsum, alpha, ps);
+            lsum += ps;
             if (KV_I8) {
                 // the probabilities take their token's v_scale before they are rounded to bf16
 #pragma unroll
