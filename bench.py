@@ -27,6 +27,20 @@ PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
 PAPER_TABLE3_MS = {2048: 96.65, 4096: 392.80}   # SlimAttention, 1 socket Xeon 8563C (paper Table 3); context only
 
 
+def measured_traffic():
+    """HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary, or {}."""
+    path = os.path.join(ROOT, "profiles", "traffic_fetch_write_c2_c4.txt")
+    out = {}
+    try:
+        for ln in open(path):
+            if ln.startswith("traffic_bytes "):
+                _, key, val = ln.split()
+                out[key] = int(float(val))
+    except OSError:
+        pass
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -34,6 +48,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the INT8 prefill workloads reported beside the headline")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="before the steps, run one plain 256 MiB device copy (a kernel of known HBM traffic) so that a "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run of this command can be scaled")
     ap.add_argument("--only", choices=["all", "prefill", "decode", "quant"], default="all",
                     help="run only one kernel per step (for profiling); the JSON line then carries only its fields")
     args = ap.parse_args()
@@ -97,6 +114,13 @@ def main():
         if ev is not None:
             ev[3].record()
 
+    if args.traffic_probe:
+        src = torch.empty((256 << 20,), dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)        # reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -130,7 +154,7 @@ def main():
                         "paper_cpu_ms_context": PAPER_TABLE3_MS[2048]},
             "roofline": {"kernel": "slim_prefill_kernel<128,bf16 kv,bf16 out>", "bound": "mfma", "achieved": round(tfl, 2),
                          "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tfl / PEAK_BF16_TFLOPS, 4),
-                         "traffic": None},
+                         "traffic": measured_traffic().get("prefill_c2")},
         })
     if do_decode:
         dbytes = acct.decode_bytes(c4.batch, c4.q_heads, c4.kv_heads, c4.seq_len, c4.head_dim)
@@ -140,7 +164,8 @@ def main():
                           "frac_of_hbm_peak": round(gbps / PEAK_HBM_GBPS, 4)}
         line["roofline_decode"] = {"kernel": "slim_decode_int8_split_kernel<128> + slim_decode_combine_kernel<128>",
                                    "bound": "hbm", "achieved": round(gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                                   "frac": round(gbps / PEAK_HBM_GBPS, 4), "traffic": None}
+                                   "frac": round(gbps / PEAK_HBM_GBPS, 4),
+                                   "traffic": measured_traffic().get("decode_c4")}
         if not do_prefill:
             line.update({"value": round(gbps, 1), "unit": "GB/s"})
     if do_quant:
