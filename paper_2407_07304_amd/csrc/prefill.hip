@@ -204,11 +204,35 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void slim_prefill_kernel(const 
 
         // prologue: steps 0 and 1 into the ring, step 2 into registers
         __syncthreads();   // the previous pass has finished reading the ring
-        load_step(0);
-        store_step(0);
-        load_step(min(1, n_steps - 1));
-        store_step(1);
-        load_step(min(2, n_steps - 1));
+        // (the three loads are issued together, so the pass pays one memory latency, not three)
+        {
+            u32x4 k0[NCH], v0[NCH], k1[NCH], v1[NCH];
+            float s0 = 0.0f, s1 = 0.0f;
+            load_step(0);
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) { k0[i] = kst[i]; v0[i] = vst[i]; }
+            s0 = sst;
+            load_step(min(1, n_steps - 1));
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) { k1[i] = kst[i]; v1[i] = vst[i]; }
+            s1 = sst;
+            load_step(min(2, n_steps - 1));
+            u32x4 k2[NCH], v2[NCH];
+            const float s2 = sst;
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) { k2[i] = kst[i]; v2[i] = vst[i]; }
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) { kst[i] = k0[i]; vst[i] = v0[i]; }
+            sst = s0;
+            store_step(0);
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) { kst[i] = k1[i]; vst[i] = v1[i]; }
+            sst = s1;
+            store_step(1);
+#pragma unroll
+            for (int i = 0; i < NCH; ++i) { kst[i] = k2[i]; vst[i] = v2[i]; }
+            sst = s2;
+        }
         __syncthreads();
         // Steady-state step k of this wave (k is below its diagonal, no mask).  The instruction order is
         // fixed by hand (sched_barrier) for a wave that runs alone on its SIMD:
