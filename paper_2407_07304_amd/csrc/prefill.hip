@@ -40,6 +40,7 @@ struct PrefillParams {
     const float* vs;
     void* out;
     int Hq, Hkv, S, causal, n_rb, n_pair, total, chunk;
+    int single, local_heads, per_xcd;   // single != 0: one row block per workgroup (small grids)
     float scale_log2e;
 };
 
@@ -76,13 +77,31 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void slim_prefill_kernel(const 
     __shared__ __attribute__((aligned(16))) uint16_t Vs[kNS][kBC * LDKV];
     __shared__ __attribute__((aligned(16))) float scS[kNS][2 * kBC];   // INT8: [0,32) k_scale*c, [32,64) v_scale
 
-    // workgroup -> (batch*head, pair): consecutive virtual ids share K/V and are sent to the
-    // same XCD (hardware deals workgroup ids round-robin over the 8 XCDs).
-    const int n = blockIdx.x;
-    const int vid = (n % 8) * p.chunk + n / 8;
-    if (vid >= p.total) return;
-    const int bh = vid / p.n_pair;
-    const int x = vid % p.n_pair;
+    // workgroup -> (batch*head, row-block pair).  Hardware deals workgroup ids round-robin over the 8
+    // XCDs, so consecutive virtual ids (which share K/V) are steered to one XCD.
+    // Small grids (fewer pairs than two workgroups per compute unit) run one row block per workgroup
+    // instead: inside an XCD the hardware fills its 32 compute units once before any gets a second
+    // workgroup, so the local index j is laid out as a snake over rows of 32 through the heavy-first
+    // list, and the two workgroups that share a compute unit carry a long and a short row block.
+    int bh, x, rb_single = 0;
+    {
+        const int n = blockIdx.x;
+        if (p.single) {
+            const int xcd = n % 8, j = n / 8;
+            if (j >= p.per_xcd) return;
+            const int r = j / 32, cpos = j % 32;
+            const int row_len = min(32, p.per_xcd - r * 32);
+            const int rank = r * 32 + ((r & 1) ? row_len - 1 - cpos : cpos);
+            rb_single = p.n_rb - 1 - rank / p.local_heads;
+            bh = xcd * p.local_heads + rank % p.local_heads;
+            x = 0;
+        } else {
+            const int vid = (n % 8) * p.chunk + n / 8;
+            if (vid >= p.total) return;
+            bh = vid / p.n_pair;
+            x = vid % p.n_pair;
+        }
+    }
     const int b = bh / p.Hq, h = bh % p.Hq;
     const int g = h / (p.Hq / p.Hkv);
     const int S = p.S;
@@ -178,8 +197,8 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void slim_prefill_kernel(const 
         return st;
     };
 
-    for (int pass = 0; pass < 2; ++pass) {
-        const int rb = pass == 0 ? p.n_rb - 1 - x : x;
+    for (int pass = 0; pass < (p.single ? 1 : 2); ++pass) {
+        const int rb = p.single ? rb_single : (pass == 0 ? p.n_rb - 1 - x : x);
         if (pass == 1 && rb == p.n_rb - 1 - x) break;   // the middle row block of an odd count
         const int i0 = rb * kBR;
         const int my_q = i0 + 32 * w + l32;             // this lane's query row (may be >= S in the last block)
@@ -481,7 +500,8 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void slim_prefill_kernel(const 
 
 template <int D, bool KV_I8, bool OUT_F32>
 static hipError_t launch_one(const PrefillParams& p, hipStream_t stream) {
-    hipLaunchKernelGGL((slim_prefill_kernel<D, KV_I8, OUT_F32>), dim3((unsigned)(8 * p.chunk)), dim3(kPrefillThreads), 0,
+    const unsigned grid = (unsigned)(8 * (p.single ? p.per_xcd : p.chunk));
+    hipLaunchKernelGGL((slim_prefill_kernel<D, KV_I8, OUT_F32>), dim3(grid), dim3(kPrefillThreads), 0,
                        stream, p);
     return hipGetLastError();
 }
@@ -502,6 +522,11 @@ hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream) {
     p.n_pair = (p.n_rb + 1) / 2;
     p.total = a.batch * a.q_heads * p.n_pair;
     p.chunk = (p.total + 7) / 8;
+    // fewer pairs than two workgroups per compute unit (256 CUs): one row block per workgroup
+    const int n_bh = a.batch * a.q_heads;
+    p.single = (p.causal && n_bh % 8 == 0 && p.n_rb > 1 && p.total < 512) ? 1 : 0;
+    p.local_heads = n_bh / 8;
+    p.per_xcd = p.local_heads * p.n_rb;
     p.scale_log2e = a.softmax_scale * kLog2e;
     const int sel = (a.head_dim == 128 ? 4 : 0) | (a.kv_int8 ? 2 : 0) | (a.out_f32 ? 1 : 0);
     switch (sel) {
