@@ -216,3 +216,74 @@ def test_gpu_quantiser_feeds_gpu_attention(sa, oracle):
     ovc, ovs = oracle.kv_quant_int8(v)
     want = oracle.attn(q, okc, ovc, scale, True, k_scale=oks, v_scale=ovs)
     check_close(host_f64(out), want, "quantise -> prefill")
+
+
+def test_kv_quant_bit_exact_every_bf16_value_against_many_scales(sa, oracle):
+    # Rows [amax, x_1 .. x_127]: for 1024 amax values (every exponent a normal bf16 amax can take, random
+    # mantissas, plus subnormal and huge ones) the rows together enumerate every bf16 x with |x| <= amax,
+    # both signs.  This walks the quantiser through every quotient x/scale it can meet, near-ties included.
+    rng = np.random.default_rng(33)
+    amax_bits = np.unique(np.concatenate([
+        rng.integers(0x0080, 0x7f00, 900), rng.integers(0x0001, 0x0080, 60), np.array([0x7f7f, 0x0001, 0x3f80, 0x42fe])
+    ]).astype(np.uint16))[:1024]
+    rows = []
+    for ab in amax_bits.tolist():
+        xs = np.arange(0, ab + 1, dtype=np.uint32)          # every non-negative bf16 up to amax
+        if xs.size > 8128:                                   # subsample large ranges, keep the top of the range dense
+            xs = np.unique(np.concatenate([rng.choice(xs, 6000, replace=False), xs[-2128:]]))
+        signs = rng.integers(0, 2, xs.size).astype(np.uint32) << 15
+        vals = (xs | signs).astype(np.uint16)
+        pad = (-vals.size) % 127
+        vals = np.concatenate([vals, np.zeros(pad, dtype=np.uint16)]).reshape(-1, 127)
+        rows.append(np.concatenate([np.full((vals.shape[0], 1), ab, dtype=np.uint16), vals], axis=1))
+    bits = np.concatenate(rows, axis=0)
+    bits = bits[: (bits.shape[0] // 4) * 4].reshape(1, 4, -1, 128)
+    print("kv_quant exhaustive-style rows", bits.shape, flush=True)
+    _quant_both(sa, oracle, np.ascontiguousarray(bits))
+
+
+def test_prefill_int8_with_all_zero_tokens(sa, oracle):
+    # a token whose K (or V) row is all zeros quantises to scale 0 and codes 0: it must act as a zero vector
+    rng = np.random.default_rng(62)
+    B, Hq, Hkv, S, D = 1, 2, 2, 200, 128
+    q, k, v = normal_bf16(rng, (B, Hq, S, D)), normal_bf16(rng, (B, Hkv, S, D)), normal_bf16(rng, (B, Hkv, S, D))
+    k[0, 0, 5] = 0
+    k[0, 1, 0] = 0
+    v[0, 0, 7] = 0
+    v[0, 1, 199] = 0
+    kc, ks = oracle.kv_quant_int8(k)
+    vc, vs = oracle.kv_quant_int8(v)
+    assert ks[0, 0, 5] == 0 and vs[0, 1, 199] == 0
+    scale = 1.0 / math.sqrt(D)
+    out = sa.slim_attn_prefill(dev_bf16(q), dev(kc), dev(vc), scale, True, k_scale=dev(ks), v_scale=dev(vs))
+    dec = sa.slim_attn_decode_int8(dev_bf16(np.ascontiguousarray(q[:, :, S - 1:S])), dev(kc), dev(ks), dev(vc), dev(vs), scale)
+    torch.cuda.synchronize()
+    want = oracle.attn(q, kc, vc, scale, True, k_scale=ks, v_scale=vs)
+    check_close(host_f64(out), want, "prefill with zero tokens")
+    check_close(host_f64(dec)[:, :, 0], want[:, :, S - 1], "decode with zero tokens")
+
+
+def test_prefill_large_scores_and_repeat_runs_are_bit_identical(sa, oracle):
+    # scores far from zero (softmax scale 1.0 on N(0,1) data with D=64 gives |s| up to ~40): the lazy
+    # running max must still track them; two launches must agree bit for bit
+    rng = np.random.default_rng(63)
+    B, Hq, Hkv, S, D = 1, 4, 2, 700, 64
+    q, k, v = normal_bf16(rng, (B, Hq, S, D)), normal_bf16(rng, (B, Hkv, S, D)), normal_bf16(rng, (B, Hkv, S, D))
+    o1 = sa.slim_attn_prefill(dev_bf16(q), dev_bf16(k), dev_bf16(v), 1.0, True, out_dtype=torch.float32)
+    o2 = sa.slim_attn_prefill(dev_bf16(q), dev_bf16(k), dev_bf16(v), 1.0, True, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2)
+    check_close(host_f64(o1), oracle.attn(q, k, v, 1.0, True), "prefill, softmax scale 1.0")
+    on = sa.slim_attn_prefill(dev_bf16(q), dev_bf16(k), dev_bf16(v), 1.0, False, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    check_close(host_f64(on), oracle.attn(q, k, v, 1.0, False), "non-causal prefill, softmax scale 1.0")
+
+
+def test_prefill_batched_gqa_full_tensor(sa, oracle):
+    rng = np.random.default_rng(64)
+    B, Hq, Hkv, S, D = 3, 8, 2, 385, 128
+    q, k, v = normal_bf16(rng, (B, Hq, S, D)), normal_bf16(rng, (B, Hkv, S, D)), normal_bf16(rng, (B, Hkv, S, D))
+    scale = 1.0 / math.sqrt(D)
+    out = sa.slim_attn_prefill(dev_bf16(q), dev_bf16(k), dev_bf16(v), scale, True)
+    torch.cuda.synchronize()
+    check_close(host_f64(out), oracle.attn(q, k, v, scale, True), "batched GQA prefill")
