@@ -217,16 +217,16 @@ def main():
     # ---- the CPU oracle on this host's cores, beside the GPU number (a baseline, not a target)
     if not args.no_cpu_baseline and do_prefill:
         import oracle
-        n_heads = 8                                   # a bounded sample: 8 of the 32 heads, every row
+        n_heads = c2.q_heads                          # the whole C2 tensor: under a second of CPU work on the box
         t0 = time.perf_counter()
         oracle.attn(q2h[:, :n_heads], k2h[:, :n_heads], v2h[:, :n_heads], c2.softmax_scale, True)
         dt = time.perf_counter() - t0
         fl = acct.prefill_flops(c2.batch, n_heads, c2.seq_len, c2.head_dim, True)
         line["cpu_baseline"] = {"value": round(fl / dt / 1e12, 5), "unit": "TFLOP/s", "cores": oracle.num_threads(),
                                 "kind": "oracle", "seconds": round(dt, 3),
-                                "sample": "heads 0-7 of the 32 heads of C2, all 2048 rows (fp64 scalar C, OpenMP)"}
+                                "sample": "the whole C2 tensor: 32 heads, 2048 rows (fp64 scalar C, OpenMP)"}
         if do_decode:
-            nb = 2
+            nb = c4.batch
             kc, ks, vc, vs = (t[:nb].cpu().numpy() for t in (kc4, ks4, vc4, vs4))
             t0 = time.perf_counter()
             oracle.attn(q4h[:nb], kc, vc, c4.softmax_scale, False, k_scale=ks, v_scale=vs)
@@ -234,7 +234,7 @@ def main():
             by = acct.decode_bytes(nb, c4.q_heads, c4.kv_heads, c4.seq_len, c4.head_dim)
             line["cpu_baseline_decode"] = {"value": round(by / dt / 1e9, 3), "unit": "GB/s",
                                            "cores": oracle.num_threads(), "kind": "oracle", "seconds": round(dt, 3),
-                                           "sample": "sequences 0-1 of the 16 of C4, all heads, all 8192 tokens"}
+                                           "sample": "the whole C4 step: 16 sequences, 32 heads, 8192 tokens"}
     print(json.dumps(line))
 
 
