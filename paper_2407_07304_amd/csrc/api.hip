@@ -24,6 +24,8 @@ int check_shape(int batch, int q_heads, int kv_heads, int len, int head_dim) {
     if (head_dim != 64 && head_dim != 128) return SLIM_ERR_UNSUPPORTED;
     if (too_large(batch, q_heads, len)) return SLIM_ERR_SHAPE;   // rows of Q/O (and of K/V, kv_heads <= q_heads)
     if (q_heads > 65535 || batch > 65535) return SLIM_ERR_SHAPE;
+    // one head's K (or V) slab, plus the tiles the prefill kernel prefetches past it, is addressed with 32 bits
+    if (((long)len + 256) * head_dim * 2 > 0xffffffffL) return SLIM_ERR_SHAPE;
     return SLIM_OK;
 }
 

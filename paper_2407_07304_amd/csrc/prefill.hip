@@ -1,25 +1,33 @@
 // Prefill attention (paper section 2.1): one work item owns a block of query rows and the
-// whole softmax direction; K/V stream through it in 32-key steps while an fp32 running max
+// whole softmax direction; K/V stream through it in 32-key tiles while an fp32 running max
 // and sum keep the softmax exact.  INT8 K/V (section 2.2) are widened exactly to bf16 while
 // being staged; their per-token scales multiply the fp32 score column (K) and the
 // probability before it is rounded to bf16 (V), so dequantisation adds no rounding.
 //
 // Mapping on gfx950 (wave64, v_mfma_f32_32x32x16_bf16):
-//   - 4 waves per workgroup, 32 query rows per wave, 128 rows per row block.  Under the
-//     causal mask a workgroup takes the row-block pair (n-1-x, x) one after the other, so
-//     every workgroup does the same amount of work.
+//   - A workgroup is 8 waves and owns 128 query rows.  Waves w and w+4 sit on the same SIMD
+//     and own the same 32 rows; the first four waves (group 0) take the even key tiles, the
+//     other four (group 1) the odd ones, each with its own running max, sum and accumulator,
+//     merged once at the end of the row block.
+//   - The two groups run in opposite phases, one barrier per phase: while one group does the
+//     softmax of its tile on the vector ALU, the other feeds the matrix pipe (P V of its last
+//     tile, then the score tile two tiles ahead).  A SIMD therefore always holds one wave that
+//     wants the vector ALU and one that wants the MFMA unit.
 //   - The score tile is computed transposed, S^T = K Q^T: the K tile is the A operand
-//     (from LDS), Q^T the B operand (held in registers for the whole pass).  In the
+//     (from LDS), Q^T the B operand (held in registers for the whole row block).  In the
 //     result every lane holds ONE query column and 16 of the 32 keys, so the row max and
 //     row sum are in-lane reductions plus one exchange between lanes l and l+32.
 //   - The same registers, rounded to bf16, are directly the B operand of
 //     O^T += V^T P^T; V^T comes from the row-major V tile in LDS through the LDS
 //     transpose read (ds_read_b64_tr_b16), so V is never transposed in memory.
 //   - O^T accumulators: lane = query column, so the online-softmax rescale is a per-lane
-//     scalar multiply, skipped while no row's max moves.
-//   - Software pipeline: the score MFMAs of step k+1 are issued before the softmax of
-//     step k, so the matrix pipe works while the vector ALU does the exponentials; a
-//     three-deep LDS ring is filled through registers one step ahead, one barrier per step.
+//     scalar multiply; the running max is lazy (it moves only when a row's max grew by more
+//     than 2^8), so the rescale runs a few times per row block.
+//   - K/V tiles reach a four-slot LDS ring through registers: all 512 threads load one
+//     16-byte piece per tile two phases before they store it, and a tile is stored two
+//     phases before it is read.
+//   - Under the causal mask a workgroup takes the row-block pair (n-1-x, x) one after the
+//     other, so every workgroup does the same amount of work.
 #include <type_traits>
 
 #include "slim_common.h"
@@ -27,10 +35,10 @@
 
 namespace slim {
 
-constexpr int kBR = 128;   // query rows per row block (4 waves x 32)
-constexpr int kBC = 32;    // keys per step
-constexpr int kNS = 3;     // LDS ring depth
-constexpr int kPrefillThreads = 256;
+constexpr int kBR = 128;   // query rows per row block (4 row groups x 32)
+constexpr int kBC = 32;    // keys per tile
+constexpr int kRing = 4;   // LDS ring depth (tiles)
+constexpr int kPrefillThreads = 512;
 
 struct PrefillParams {
     const uint16_t* q;
@@ -40,7 +48,6 @@ struct PrefillParams {
     const float* vs;
     void* out;
     int Hq, Hkv, S, causal, n_rb, n_pair, total, chunk;
-    int single, local_heads, per_xcd;   // single != 0: one row block per workgroup (small grids)
     float scale_log2e;
 };
 
@@ -63,87 +70,80 @@ __device__ __forceinline__ float half_sum(float x) {
     return __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
 }
 
+template <int N>
+using int_c = std::integral_constant<int, N>;
+
 template <int D, bool KV_I8, bool OUT_F32>
-__global__ __launch_bounds__(kPrefillThreads, 1) void slim_prefill_kernel(const PrefillParams p) {
+__global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const PrefillParams p) {
     constexpr int KS = D / 16;       // k-steps of the score MFMA
     constexpr int DT = D / 32;       // 32-row tiles of O^T
     constexpr int LDKK = D + 8;      // K rows: 16 B of padding, conflict-free 128-bit row reads
     constexpr int LDKV = D + 32;     // V rows: 64 B of padding, conflict-free transpose reads
-    constexpr int CPR = KV_I8 ? D / 16 : D / 8;                  // 16-byte chunks per row
-    constexpr int NCHUNK = kBC * CPR;                            // chunks per step and tensor
-    constexpr int NCH = (NCHUNK + kPrefillThreads - 1) / kPrefillThreads;
+    constexpr int ROWB = KV_I8 ? D : 2 * D;   // bytes per K/V row in memory
+    constexpr int CPR = ROWB / 16;            // 16-byte pieces per row
+    constexpr int CH = kBC * CPR;             // pieces per tile and tensor: 512, 256 or 128
+    constexpr int KSLOT = kBC * LDKK, VSLOT = kBC * LDKV;   // elements per ring slot
+    constexpr int K_BYTES = kRing * KSLOT * 2, V_BYTES = kRing * VSLOT * 2;
+    constexpr int NV = DT / 2 * 4 + 1;   // f32x4 vectors a wave hands to its partner at the merge
+    static_assert(8 * NV * 64 * 16 <= K_BYTES + V_BYTES, "merge buffer must fit in the ring");
 
-    __shared__ __attribute__((aligned(16))) uint16_t Ks[kNS][kBC * LDKK];
-    __shared__ __attribute__((aligned(16))) uint16_t Vs[kNS][kBC * LDKV];
-    __shared__ __attribute__((aligned(16))) float scS[kNS][2 * kBC];   // INT8: [0,32) k_scale*c, [32,64) v_scale
+    __shared__ __attribute__((aligned(16))) char smem[K_BYTES + V_BYTES + kRing * 2 * kBC * 4];
+    uint16_t* const Ks = reinterpret_cast<uint16_t*>(smem);
+    uint16_t* const Vs = reinterpret_cast<uint16_t*>(smem + K_BYTES);
+    float* const scS = reinterpret_cast<float*>(smem + K_BYTES + V_BYTES);   // INT8: per slot [0,32) k_scale*c, [32,64) v_scale
 
     // workgroup -> (batch*head, row-block pair).  Hardware deals workgroup ids round-robin over the 8
     // XCDs, so consecutive virtual ids (which share K/V) are steered to one XCD.
-    // Small grids (fewer pairs than two workgroups per compute unit) run one row block per workgroup
-    // instead: inside an XCD the hardware fills its 32 compute units once before any gets a second
-    // workgroup, so the local index j is laid out as a snake over rows of 32 through the heavy-first
-    // list, and the two workgroups that share a compute unit carry a long and a short row block.
-    int bh, x, rb_single = 0;
+    int bh, x;
     {
-        const int n = blockIdx.x;
-        if (p.single) {
-            const int xcd = n % 8, j = n / 8;
-            if (j >= p.per_xcd) return;
-            const int r = j / 32, cpos = j % 32;
-            const int row_len = min(32, p.per_xcd - r * 32);
-            const int rank = r * 32 + ((r & 1) ? row_len - 1 - cpos : cpos);
-            rb_single = p.n_rb - 1 - rank / p.local_heads;
-            bh = xcd * p.local_heads + rank % p.local_heads;
-            x = 0;
-        } else {
-            const int vid = (n % 8) * p.chunk + n / 8;
-            if (vid >= p.total) return;
-            bh = vid / p.n_pair;
-            x = vid % p.n_pair;
-        }
+        const int n = (int)__builtin_amdgcn_workgroup_id_x();   // the builtin, not a library call: stays a scalar
+        const int vid = (n % 8) * p.chunk + n / 8;
+        if (vid >= p.total) return;
+        bh = vid / p.n_pair;
+        x = vid % p.n_pair;
     }
     const int b = bh / p.Hq, h = bh % p.Hq;
     const int g = h / (p.Hq / p.Hkv);
     const int S = p.S;
     const float c = p.scale_log2e;
 
-    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, l32 = l & 31, hh = l >> 5;
+    // wave index as a scalar: everything derived from it (group, row group, last tile) stays uniform
+    const int tid = (int)__builtin_amdgcn_workitem_id_x(), w8 = __builtin_amdgcn_readfirstlane(tid >> 6), grp = w8 >> 2, w = w8 & 3;
+    const int l = tid & 63, l32 = l & 31, hh = l >> 5;
     const long kvrow0 = ((long)b * p.Hkv + g) * (long)S;
 
-    // ---- staging: global -> registers (one step ahead) -> LDS ring
-    // Addresses: a uniform base (this head's K / V slab) plus a 32-bit per-thread offset, so the loads
-    // take the scalar-base form; the LDS destinations are a per-thread constant plus the ring slot.
-    constexpr int ROWB = KV_I8 ? D : 2 * D;   // bytes per K/V row in memory
-    const char* kslab = (const char*)p.k + kvrow0 * ROWB;
-    const char* vslab = (const char*)p.v + kvrow0 * ROWB;
-    const float* ksslab = KV_I8 ? p.ks + kvrow0 : nullptr;
-    const float* vsslab = KV_I8 ? p.vs + kvrow0 : nullptr;
-    int st_row[NCH], st_colb[NCH], st_kdst[NCH], st_vdst[NCH];
+    // ---- staging: global -> registers -> LDS ring.  Buffer loads: the descriptor covers exactly this
+    // head's K (V) slab, the offset is a per-thread constant plus the tile offset, and pieces past the
+    // end of the sequence read as zero (those keys are masked in the softmax).
+    const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)((const char*)p.k + kvrow0 * ROWB), 0, (int)((unsigned)S * ROWB), 0x00020000);
+    const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc(
+        (void*)((const char*)p.v + kvrow0 * ROWB), 0, (int)((unsigned)S * ROWB), 0x00020000);
+    const float* sslab = KV_I8 ? ((l < kBC ? p.ks : p.vs) + kvrow0) : nullptr;
+    // A tile (CH 16-byte pieces per tensor) is staged by the four waves of ONE group: piece gl + 256 i of
+    // thread gl.  The last wave of a group also carries the tile's 32 + 32 scales (INT8).
+    constexpr int NP = CH >= 256 ? CH / 256 : 1;
+    const int gl = tid & 255;
+    const bool has_p = CH >= 256 || w < CH / 64;
+    const bool has_s = KV_I8 && w == 3;   // lanes 0..31: k_scale of key l, lanes 32..63: v_scale of key l-32
+    unsigned p_off[NP];
+    int p_kdst[NP], p_vdst[NP];
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-        const int cidx = tid + kPrefillThreads * i;
-        st_row[i] = cidx / CPR;
-        st_colb[i] = (cidx % CPR) * 16;
-        st_kdst[i] = st_row[i] * LDKK + (cidx % CPR) * (KV_I8 ? 16 : 8);
-        st_vdst[i] = st_row[i] * LDKV + (cidx % CPR) * (KV_I8 ? 16 : 8);
+    for (int i = 0; i < NP; ++i) {
+        const int pid = gl + 256 * i, row = pid / CPR, col = pid % CPR;
+        p_off[i] = (unsigned)row * ROWB + (unsigned)col * 16u;
+        p_kdst[i] = row * LDKK + col * (KV_I8 ? 16 : 8);
+        p_vdst[i] = row * LDKV + col * (KV_I8 ? 16 : 8);
     }
-    u32x4 kst[NCH], vst[NCH];
-    float sst = 0.0f;
-    auto load_step = [&](int s) {
-        const int j0 = s * kBC;
+    auto load_tile = [&](const __amdgpu_buffer_rsrc_t rs, int t, u32x4 (&dst)[NP]) {
+        if (has_p) {
 #pragma unroll
-        for (int i = 0; i < NCH; ++i) {
-            if (NCHUNK % kPrefillThreads == 0 || tid + kPrefillThreads * i < NCHUNK) {
-                // rows past the end of the sequence: clamped here, masked in the softmax
-                const unsigned off = (unsigned)min(j0 + st_row[i], S - 1) * (unsigned)ROWB + (unsigned)st_colb[i];
-                kst[i] = *reinterpret_cast<const u32x4*>(kslab + off);
-                vst[i] = *reinterpret_cast<const u32x4*>(vslab + off);
-            }
+            for (int i = 0; i < NP; ++i)
+                dst[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)((unsigned)t * (kBC * ROWB) + p_off[i]), 0, 0);
         }
-        if (KV_I8) {
-            if (tid < kBC) sst = ksslab[min(j0 + tid, S - 1)];
-            else if (tid < 2 * kBC) sst = vsslab[min(j0 + tid - kBC, S - 1)];
-        }
+    };
+    auto load_s = [&](int t, float& dst) {
+        if (has_s) dst = sslab[min(t * kBC + l32, S - 1)];
     };
     auto widen16 = [&](const u32x4 cw, uint16_t* dst) {   // 16 INT8 codes -> 16 bf16 (exact)
         u32x4 lo, hi;
@@ -157,25 +157,21 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void slim_prefill_kernel(const 
         *reinterpret_cast<u32x4*>(dst) = lo;
         *reinterpret_cast<u32x4*>(dst + 8) = hi;
     };
-    auto store_step = [&](int buf) {
-        uint16_t* kdst = &Ks[0][0] + buf * (kBC * LDKK);
-        uint16_t* vdst = &Vs[0][0] + buf * (kBC * LDKV);
+    auto store_tile = [&](uint16_t* slot_base, const int (&dsts)[NP], const u32x4 (&src)[NP]) {
+        if (has_p) {
 #pragma unroll
-        for (int i = 0; i < NCH; ++i) {
-            if (NCHUNK % kPrefillThreads == 0 || tid + kPrefillThreads * i < NCHUNK) {
-                if (KV_I8) {
-                    widen16(kst[i], kdst + st_kdst[i]);
-                    widen16(vst[i], vdst + st_vdst[i]);
-                } else {
-                    *reinterpret_cast<u32x4*>(kdst + st_kdst[i]) = kst[i];
-                    *reinterpret_cast<u32x4*>(vdst + st_vdst[i]) = vst[i];
-                }
+            for (int i = 0; i < NP; ++i) {
+                if (KV_I8) widen16(src[i], slot_base + dsts[i]);
+                else *reinterpret_cast<u32x4*>(slot_base + dsts[i]) = src[i];
             }
         }
-        if (KV_I8) {
-            if (tid < kBC) scS[buf][tid] = sst * c;
-            else if (tid < 2 * kBC) scS[buf][tid] = sst;
-        }
+    };
+    auto store_s = [&](int slot, float s) {
+        if (has_s) scS[slot * (2 * kBC) + l] = l < kBC ? s * c : s;
+    };
+    struct Stage {
+        u32x4 k[NP], v[NP];
+        float s;
     };
 
     bf16x8 qreg[KS];
@@ -183,30 +179,18 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void slim_prefill_kernel(const 
     const int ka_off = l32 * LDKK + 8 * hh;                                              // K fragment (row l32)
     const int va_off = (4 * hh + (l & 15) / 4) * LDKV + 16 * ((l >> 4) & 1) + 4 * (l & 3);   // V transpose read
 
-    // S^T[key][query] = sum_d K[key][d] Q[query][d] for the 32 keys of a step
-    auto score = [&](int buf) {
-        f32x16 st;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) st[r] = 0.0f;
-        const uint16_t* ka = &Ks[0][0] + buf * (kBC * LDKK) + ka_off;
-#pragma unroll
-        for (int s = 0; s < KS; ++s) {
-            const bf16x8 a = *reinterpret_cast<const bf16x8*>(ka + 16 * s);
-            st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qreg[s], st, 0, 0, 0);
-        }
-        return st;
-    };
-
-    for (int pass = 0; pass < (p.single ? 1 : 2); ++pass) {
-        const int rb = p.single ? rb_single : (pass == 0 ? p.n_rb - 1 - x : x);
+    for (int pass = 0; pass < 2; ++pass) {
+        const int rb = pass == 0 ? p.n_rb - 1 - x : x;
         if (pass == 1 && rb == p.n_rb - 1 - x) break;   // the middle row block of an odd count
         const int i0 = rb * kBR;
         const int my_q = i0 + 32 * w + l32;             // this lane's query row (may be >= S in the last block)
         const int wave_q_lo = i0 + 32 * w;
         const int kend = p.causal ? min(S, i0 + kBR) : S;
-        const int n_steps = (kend + kBC - 1) / kBC;
-        // last step this wave computes: its diagonal step under the causal mask; none if it has no row
-        const int wave_last = wave_q_lo >= S ? -1 : (p.causal ? min(n_steps - 1, wave_q_lo / kBC) : n_steps - 1);
+        const int n_tiles = (kend + kBC - 1) / kBC;
+        const int last_phase = 2 * ((n_tiles + 1) / 2);   // phases 0..last_phase, one barrier each
+        // last tile of this row group: its diagonal under the causal mask, else the tail of the key axis
+        // (always taken through the masked path); -1 if the row group lies past the sequence
+        const int t_last = wave_q_lo >= S ? -1 : (p.causal ? min(n_tiles - 1, wave_q_lo / kBC) : n_tiles - 1);
         const int lim = p.causal ? min(my_q, S - 1) : S - 1;   // last key this lane's row may see
 
         // Q^T B-operands: lane holds row my_q, d = 16 s + 8 hh + [0,8)
@@ -219,279 +203,307 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void slim_prefill_kernel(const 
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
             for (int r = 0; r < 16; ++r) o[dt][r] = 0.0f;
-        float m = kMasked, lsum = 0.0f;   // bf16 K/V: m in raw score units; INT8: in scaled (log2) units
+        float M = kMasked, lsum = 0.0f;   // running max in scaled (log2) units; per-lane partial row sum
 
-        // prologue: steps 0 and 1 into the ring, step 2 into registers
-        __syncthreads();   // the previous pass has finished reading the ring
-        // (the three loads are issued together, so the pass pays one memory latency, not three)
+        // ---- prologue: K tiles 0..2 and V tile 0 into the ring (group 0: K 0, V 0; group 1: K 1, K 2), and
+        // into registers the tiles each group stores in its first matrix phase (group 1 in phase 0: K 3,
+        // V 1; group 0 in phase 1: K 4, V 2).  All loads are issued together.
+        Stage sg;
         {
-            u32x4 k0[NCH], v0[NCH], k1[NCH], v1[NCH];
+            u32x4 pa[NP], pb[NP];
             float s0 = 0.0f, s1 = 0.0f;
-            load_step(0);
-#pragma unroll
-            for (int i = 0; i < NCH; ++i) { k0[i] = kst[i]; v0[i] = vst[i]; }
-            s0 = sst;
-            load_step(min(1, n_steps - 1));
-#pragma unroll
-            for (int i = 0; i < NCH; ++i) { k1[i] = kst[i]; v1[i] = vst[i]; }
-            s1 = sst;
-            load_step(min(2, n_steps - 1));
-            u32x4 k2[NCH], v2[NCH];
-            const float s2 = sst;
-#pragma unroll
-            for (int i = 0; i < NCH; ++i) { k2[i] = kst[i]; v2[i] = vst[i]; }
-#pragma unroll
-            for (int i = 0; i < NCH; ++i) { kst[i] = k0[i]; vst[i] = v0[i]; }
-            sst = s0;
-            store_step(0);
-#pragma unroll
-            for (int i = 0; i < NCH; ++i) { kst[i] = k1[i]; vst[i] = v1[i]; }
-            sst = s1;
-            store_step(1);
-#pragma unroll
-            for (int i = 0; i < NCH; ++i) { kst[i] = k2[i]; vst[i] = v2[i]; }
-            sst = s2;
+            if (grp == 0) {
+                load_tile(krs, 0, pa);
+                load_tile(vrs, 0, pb);
+                load_s(0, s0);
+            } else {
+                load_tile(krs, 1, pa);
+                load_tile(krs, 2, pb);
+                load_s(1, s0);
+                load_s(2, s1);
+            }
+            load_tile(krs, 4 - grp, sg.k);
+            load_tile(vrs, 2 - grp, sg.v);
+            load_s(4 - grp, sg.s);
+            __syncthreads();   // the previous pass has finished with the ring and the merge buffer
+            if (grp == 0) {
+                store_tile(Ks, p_kdst, pa);
+                store_tile(Vs, p_vdst, pb);
+                store_s(0, s0);
+            } else {
+                store_tile(Ks + KSLOT, p_kdst, pa);
+                store_tile(Ks + 2 * KSLOT, p_kdst, pb);
+                store_s(1, s0);
+                store_s(2, s1);
+            }
         }
         __syncthreads();
-        // Steady-state step k of this wave (k is below its diagonal, no mask).  The instruction order is
-        // fixed by hand (sched_barrier) for a wave that runs alone on its SIMD:
-        //   K fragments of step k+1  ->  row max / alpha of step k  ->  score MFMAs of step k+1, each
-        //   followed by a slice of step k's exponentials  ->  ring traffic  ->  P V MFMAs of step k with
-        //   the V fragment reads between them.
-        auto steady_step = [&](int k, int buf, f32x16& st_cur, f32x16& st_nxt) {
-            constexpr int EPM = 16 / KS;   // exponentials issued after each score MFMA
-            const int nbuf = buf == kNS - 1 ? 0 : buf + 1;
-            const int wbuf = nbuf == kNS - 1 ? 0 : nbuf + 1;
-            bf16x8 kfr[KS];
-            {
-                const uint16_t* ka = &Ks[0][0] + nbuf * (kBC * LDKK) + ka_off;
+
+        // Operand fragments are fetched from LDS one phase ahead (by the wave's own softmax phase, which
+        // leaves the LDS pipe idle), so the matrix phase starts with its operands in registers:
+        //   kfr: K tile as A operand, lane = key l32, d = 16 s + 8 hh + [0,8)
+        //   vfr[u]: V^T tile as A operand for keys 16u..16u+15.  Transpose read: the 16 lanes of a group
+        //   fetch rows k..k+3 (4 lanes per row, 4 columns each) and lane i receives column i of those rows.
+        bf16x8 kfr[KS];
+        s16x4 vfr[2][2 * DT];
+        auto fetch_k = [&](auto slot_c) {
+            constexpr int slot = decltype(slot_c)::value;
+            const uint16_t* ka = Ks + slot * KSLOT + ka_off;
 #pragma unroll
-                for (int s = 0; s < KS; ++s) kfr[s] = *reinterpret_cast<const bf16x8*>(ka + 16 * s);
+            for (int s = 0; s < KS; ++s) kfr[s] = *reinterpret_cast<const bf16x8*>(ka + 16 * s);
+        };
+        auto fetch_v = [&](auto slot_c, auto u_c) {
+            constexpr int slot = decltype(slot_c)::value, u = decltype(u_c)::value;
+            const uint16_t* va = Vs + slot * VSLOT + va_off + 16 * u * LDKV;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                vfr[u][2 * dt] = lds_read_tr16(va + 32 * dt);
+                vfr[u][2 * dt + 1] = lds_read_tr16(va + 8 * LDKV + 32 * dt);
             }
-            float t[16];
+        };
+        // One score MFMA, S^T[key][query] += sum over d in [16 s, 16 s + 16) of K[key][d] Q[query][d], and one
+        // P V MFMA, O^T[d][query] += sum_key V[key][d] P[query][key] for d in [32 dt, 32 dt + 32); k-step u of
+        // the latter covers registers 8u..8u+7 of the probabilities, i.e. keys 16u + {4hh..4hh+3} and
+        // 16u + 8 + {4hh..4hh+3} of the tile.
+        auto score_mfma = [&](int s, f32x16& acc) {
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[s], qreg[s], acc, 0, 0, 0);
+        };
+        auto pv_mfma = [&](int u, int dt, const u32x4 (&pw)[2]) {
+            const bf16x8 pb = __builtin_bit_cast(bf16x8, pw[u]);
+            const s16x4 lo = vfr[u][2 * dt], hi = vfr[u][2 * dt + 1];
+            const s16x8 av = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+            o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb, o[dt], 0, 0, 0);
+        };
+        // softmax of tile t (scores in st, register r of this lane is key 32 t + 8 (r/4) + 4 hh + r%4):
+        // probabilities, rounded to bf16, into pw.  `full`: masked tile, recompute the max exactly.
+        // The fast path runs unconditionally (its results are dropped for a tile this row group skips) and
+        // shares its block with the LDS reads of the coming matrix phase (K tile t+2, first 16 keys of V
+        // tile t), which are spread between the vector instructions: the wave never waits on a full LDS
+        // queue, and the reads have landed when the phase ends.
+        auto softmax = [&](auto slot_c, auto kslot_c, int t, const f32x16& st, u32x4 (&pw)[2]) {
+            constexpr int slot = decltype(slot_c)::value;
+            float cf[16];
             if (KV_I8) {
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
-                    const f32x4 kf = *reinterpret_cast<const f32x4*>(&scS[buf][8 * r4 + 4 * hh]);
+                    const f32x4 kf = *reinterpret_cast<const f32x4*>(&scS[slot * (2 * kBC) + 8 * r4 + 4 * hh]);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) t[4 * r4 + e] = st_cur[4 * r4 + e] * kf[e];
+                    for (int e = 0; e < 4; ++e) cf[4 * r4 + e] = kf[e];
                 }
             } else {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) t[r] = st_cur[r];
+                for (int r = 0; r < 16; ++r) cf[r] = c;
             }
-            float mloc = fmaxf(t[0], t[1]);
+            fetch_k(kslot_c);
+            fetch_v(slot_c, int_c<0>{});
+            // Fast path: exponentials against the running max as it stands; the lane's partial sum doubles
+            // as the overflow check (lazy running max: it only moves when the sum of a lane's 16
+            // probabilities exceeds 2^8, so the accumulator is rescaled a few times per row block).
+            float a[16], ps;
+            {
+                float ps0 = 0.0f, ps1 = 0.0f;
 #pragma unroll
-            for (int r = 2; r < 16; r += 2) mloc = fmaxf(mloc, fmaxf(t[r], t[r + 1]));
-            // lazy running max: it only moves when some row's max grew by more than 2^8, so the
-            // probabilities stay below 256 and the accumulator is rescaled a few times per row block
-            const float cand = fmaxf(m, half_max(mloc));
-            const float jump = KV_I8 ? cand - m : (cand - m) * c;
-            if (__builtin_amdgcn_ballot_w64(jump > 8.0f) != 0) {
-                const float alpha = fast_exp2(KV_I8 ? m - cand : (m - cand) * c);
+                for (int r = 0; r < 16; r += 2) {
+                    a[r] = fast_exp2(fmaf(st[r], cf[r], -M));
+                    a[r + 1] = fast_exp2(fmaf(st[r + 1], cf[r + 1], -M));
+                    ps0 += a[r];
+                    ps1 += a[r + 1];
+                }
+                ps = ps0 + ps1;
+            }
+            if (KV_I8) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);   // the key scales first
+#pragma unroll
+            for (int i = 0; i < KS + 2 * DT; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+                __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);   // three vector instructions
+            }
+            if (t > t_last) {   // tile skipped by this row group: its P V MFMAs run on zeros
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) pw[u][i] = 0u;
+                return;
+            }
+            const bool full = t == t_last;   // masked tile: recompute the max exactly
+            const bool redo = full || __builtin_amdgcn_ballot_w64(ps > 256.0f) != 0;
+            if (redo) {
+                const int key0 = t * kBC + 4 * hh;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float u = st[r] * cf[r];
+                    a[r] = (!full || key0 + 8 * (r / 4) + (r % 4) <= lim) ? u : kMasked;
+                }
+                float umax = fmaxf(a[0], a[1]);
+#pragma unroll
+                for (int r = 2; r < 16; r += 2) umax = fmaxf(umax, fmaxf(a[r], a[r + 1]));
+                const float m_new = fmaxf(M, half_max(umax));
+                const float alpha = fast_exp2(M - m_new);
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
                 lsum *= alpha;
-                m = cand;
-            }
-            const float mc = KV_I8 ? m : m * c;
-            __builtin_amdgcn_sched_barrier(0);
-
-            const uint16_t* va = &Vs[0][0] + buf * (kBC * LDKV) + va_off;
-            s16x4 vlo[DT], vhi[DT];
-            float ps = 0.0f;
+                M = m_new;
+                float ps0 = 0.0f, ps1 = 0.0f;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) st_nxt[r] = 0.0f;
-#pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                st_nxt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[s], qreg[s], st_nxt, 0, 0, 0);
-#pragma unroll
-                for (int e = s * EPM; e < (s + 1) * EPM; ++e) {
-                    t[e] = KV_I8 ? fast_exp2(t[e] - mc) : fast_exp2(fmaf(t[e], c, -mc));
-                    ps += t[e];
+                for (int r = 0; r < 16; r += 2) {
+                    a[r] = fast_exp2(a[r] - m_new);
+                    a[r + 1] = fast_exp2(a[r + 1] - m_new);
+                    ps0 += a[r];
+                    ps1 += a[r + 1];
                 }
-                if (s == KS / 2) {   // V fragments of the first 16 keys, in flight under the remaining exponentials
-#pragma unroll
-                    for (int dt = 0; dt < DT; ++dt) {
-                        vlo[dt] = lds_read_tr16(va + 32 * dt);
-                        vhi[dt] = lds_read_tr16(va + 8 * LDKV + 32 * dt);
-                    }
-                }
+                ps = ps0 + ps1;
             }
             lsum += ps;
             if (KV_I8) {
                 // the probabilities take their token's v_scale before they are rounded to bf16
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
-                    const f32x4 vf = *reinterpret_cast<const f32x4*>(&scS[buf][kBC + 8 * r4 + 4 * hh]);
+                    const f32x4 vf = *reinterpret_cast<const f32x4*>(&scS[slot * (2 * kBC) + kBC + 8 * r4 + 4 * hh]);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) t[4 * r4 + e] *= vf[e];
+                    for (int e = 0; e < 4; ++e) a[4 * r4 + e] *= vf[e];
                 }
             }
-            u32x4 pw[2];
 #pragma unroll
             for (int u = 0; u < 2; ++u)
 #pragma unroll
-                for (int i = 0; i < 4; ++i) pw[u][i] = pack_bf16x2(t[8 * u + 2 * i], t[8 * u + 2 * i + 1]);
-            // ring: registers (step k+2) -> LDS, then fetch step k+3 into registers
-            store_step(wbuf);
-            load_step(min(k + 3, n_steps - 1));
-
-            // O^T[d][query] += sum_key V[key][d] P[query][key]; k-step u covers registers 8u..8u+7,
-            // i.e. keys 16u + {4hh..4hh+3} and 16u + 8 + {4hh..4hh+3} of the step
-            s16x4 wlo[DT], whi[DT];
-            const bf16x8 pb0 = __builtin_bit_cast(bf16x8, pw[0]);
-            const bf16x8 pb1 = __builtin_bit_cast(bf16x8, pw[1]);
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt) {
-                wlo[dt] = lds_read_tr16(va + 16 * LDKV + 32 * dt);
-                whi[dt] = lds_read_tr16(va + 24 * LDKV + 32 * dt);
-                const s16x8 av = {vlo[dt][0], vlo[dt][1], vlo[dt][2], vlo[dt][3], vhi[dt][0], vhi[dt][1], vhi[dt][2], vhi[dt][3]};
-                o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb0, o[dt], 0, 0, 0);
-            }
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt) {
-                const s16x8 av = {wlo[dt][0], wlo[dt][1], wlo[dt][2], wlo[dt][3], whi[dt][0], whi[dt][1], whi[dt][2], whi[dt][3]};
-                o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb1, o[dt], 0, 0, 0);
-            }
-            // instruction pipeline of the region above (one scheduling region): every score MFMA is followed
-            // by a slice of the exponentials, the ring traffic sits between the two MFMA runs, and the
-            // second half of the V fragments is read under the first P V MFMAs
-#pragma unroll
-            for (int s = 0; s < KS; ++s) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);                 // one MFMA
-                __builtin_amdgcn_sched_group_barrier(0x002, (KV_I8 ? 4 : 3) * EPM + 1, 0);   // its share of the softmax VALU work
-                if (s == KS / 2) __builtin_amdgcn_sched_group_barrier(0x100, 2 * DT, 0);   // V fragments, first 16 keys
-            }
-            __builtin_amdgcn_sched_group_barrier(0x002, 16, 0);    // row sum, packing
-            __builtin_amdgcn_sched_group_barrier(0x200, 2 * NCH * (KV_I8 ? 2 : 1), 0);   // ring: LDS writes
-            __builtin_amdgcn_sched_group_barrier(0x020, 2 * NCH, 0);                       // ring: global loads
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-            }
-            __builtin_amdgcn_sched_group_barrier(0x008, DT, 0);
-            __syncthreads();
+                for (int i = 0; i < 4; ++i) pw[u][i] = pack_bf16x2(a[8 * u + 2 * i], a[8 * u + 2 * i + 1]);
         };
-        // The wave's last step (its diagonal under the causal mask, or the tail of the key axis): masked,
-        // nothing to issue ahead.
-        auto last_step = [&](int k, int buf, f32x16& st_cur) {
-            const int wbuf = buf == 0 ? kNS - 1 : buf - 1;   // (buf + 2) mod 3
-            const int key0 = k * kBC;
-            // register r of this lane is key  key0 + 8 (r/4) + 4 hh + r%4
-            float t[16];
-            if (KV_I8) {
+
+        f32x16 st;
 #pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    const f32x4 kf = *reinterpret_cast<const f32x4*>(&scS[buf][8 * r4 + 4 * hh]);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) t[4 * r4 + e] = st_cur[4 * r4 + e] * kf[e];
-                }
+        for (int r = 0; r < 16; ++r) st[r] = 0.0f;
+        u32x4 pw[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
+
+        // One phase.  The group whose parity matches the phase does the softmax of tile phi; the other one
+        // does the matrix work of tile phi-1 (P V, and the scores of tile phi+1) and the ring traffic.
+        auto phase = [&](auto p4_c, auto grp_c, int phi) {
+            constexpr int P4 = decltype(p4_c)::value, G = decltype(grp_c)::value;
+            if constexpr ((P4 & 1) == G) {
+                const int t = phi;
+                softmax(int_c<P4>{}, int_c<(P4 + 2) & 3>{}, t, st, pw);
             } else {
+                // Matrix phase of tile t = phi - 1: its P V MFMAs and the score MFMAs of tile t + 2, always all
+                // sixteen (a skipped tile has P = 0, unused scores are dropped), alternating so that the score
+                // chain never issues two dependent MFMAs back to back.  Operands are in registers except the
+                // last 16 keys of V tile t, requested first and used from the ninth MFMA on.  The ring traffic
+                // sits in the shadow of the MFMAs: the pieces loaded two phases ago go to K tile phi+3 and V
+                // tile phi+1 after the first eight, the pieces of K tile phi+5 and V tile phi+3 are requested
+                // after the last one.
+                if (phi > 0) {
+                    fetch_v(int_c<(P4 + 3) & 3>{}, int_c<1>{});
+                } else {   // no tile -1: nothing but zeros may meet the (zero) probabilities
 #pragma unroll
-                for (int r = 0; r < 16; ++r) t[r] = st_cur[r];
+                    for (int i = 0; i < 2 * DT; ++i) vfr[1][i] = s16x4{0, 0, 0, 0};
+                }
+                f32x16 acc;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < DT; ++i) {   // (the fences keep the issue order as written)
+                    score_mfma(i, acc);
+                    __builtin_amdgcn_sched_barrier(0);
+                    pv_mfma(0, i, pw);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                store_tile(Ks + ((P4 + 3) & 3) * KSLOT, p_kdst, sg.k);
+                store_tile(Vs + ((P4 + 1) & 3) * VSLOT, p_vdst, sg.v);
+                store_s((P4 + 3) & 3, sg.s);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < DT; ++i) {
+                    score_mfma(DT + i, acc);
+                    __builtin_amdgcn_sched_barrier(0);
+                    pv_mfma(1, i, pw);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                st = acc;
+                load_tile(krs, phi + 5, sg.k);
+                load_tile(vrs, phi + 3, sg.v);
+                load_s(phi + 5, sg.s);
             }
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        auto run = [&](auto grp_c) {
+            constexpr int G = decltype(grp_c)::value;
+            // group 0 starts with the scores of tile 0; group 1 computes those of tile 1 in phase 0
+            if (G == 0) {
+                fetch_k(int_c<0>{});
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int key = key0 + 8 * (r / 4) + 4 * hh + (r % 4);
-                t[r] = (key <= lim) ? t[r] : kMasked;
+                for (int r = 0; r < 16; ++r) st[r] = 0.0f;
+#pragma unroll
+                for (int s = 0; s < KS; ++s) score_mfma(s, st);
+            } else {
+                fetch_k(int_c<1>{});
+#pragma unroll
+                for (int i = 0; i < 2 * DT; ++i) vfr[0][i] = s16x4{0, 0, 0, 0};   // phase 0 has no tile -1
             }
-            float mloc = fmaxf(t[0], t[1]);
-#pragma unroll
-            for (int r = 2; r < 16; r += 2) mloc = fmaxf(mloc, fmaxf(t[r], t[r + 1]));
-            const float m_new = fmaxf(m, half_max(mloc));
-            const float alpha = KV_I8 ? fast_exp2(m - m_new) : fast_exp2((m - m_new) * c);
-            const float mc = KV_I8 ? m_new : m_new * c;
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
-            m = m_new;
-            float ps = 0.0f;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                t[r] = KV_I8 ? fast_exp2(t[r] - mc) : fast_exp2(fmaf(t[r], c, -mc));
-                ps += t[r];
+            for (int phi = 0; phi <= last_phase; phi += 4) {
+                phase(int_c<0>{}, grp_c, phi);
+                if (phi + 1 > last_phase) break;
+                phase(int_c<1>{}, grp_c, phi + 1);
+                phase(int_c<2>{}, grp_c, phi + 2);   // last_phase is even: phases come in pairs after the first
+                if (phi + 3 > last_phase) break;
+                phase(int_c<3>{}, grp_c, phi + 3);
             }
-            lsum = fmaf(lsum, alpha, ps);
-            if (KV_I8) {
+        };
+        if (grp == 0) run(int_c<0>{});
+        else run(int_c<1>{});
+
+        // ---- merge the two groups' partial results.  A wave keeps half of its O^T tiles and hands the
+        // other half, with its max and row sum, to its partner (same rows, other group) through LDS.
+        {
+            f32x4* mg = reinterpret_cast<f32x4*>(smem);   // [wave][NV][lane]; the ring is dead after the last barrier
+            const float L = half_sum(lsum);
+            constexpr int HALF = DT / 2;
+            const int keep0 = grp == 0 ? 0 : HALF;
+#pragma unroll
+            for (int dt = 0; dt < HALF; ++dt)
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
-                    const f32x4 vf = *reinterpret_cast<const f32x4*>(&scS[buf][kBC + 8 * r4 + 4 * hh]);
+                    f32x4 vsend;
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) t[4 * r4 + e] *= vf[e];
+                    for (int e = 0; e < 4; ++e) vsend[e] = grp == 0 ? o[HALF + dt][4 * r4 + e] : o[dt][4 * r4 + e];
+                    mg[(w8 * NV + dt * 4 + r4) * 64 + l] = vsend;
                 }
-            }
-            u32x4 pw[2];
-#pragma unroll
-            for (int u = 0; u < 2; ++u)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) pw[u][i] = pack_bf16x2(t[8 * u + 2 * i], t[8 * u + 2 * i + 1]);
-            store_step(wbuf);
-            load_step(min(k + 3, n_steps - 1));
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const bf16x8 pb = __builtin_bit_cast(bf16x8, pw[u]);
-                // transpose read: the 16 lanes of a group fetch rows k..k+3 (4 lanes per row, 4 columns
-                // each) and lane i of the group receives column i of those 4 rows
-                const uint16_t* va = &Vs[0][0] + buf * (kBC * LDKV) + va_off + 16 * u * LDKV;
-#pragma unroll
-                for (int dt = 0; dt < DT; ++dt) {
-                    const s16x4 lo = lds_read_tr16(va + 32 * dt);
-                    const s16x4 hi = lds_read_tr16(va + 8 * LDKV + 32 * dt);
-                    const s16x8 av = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb, o[dt], 0, 0, 0);
-                }
+            {
+                const f32x4 ml = {M, L, 0.0f, 0.0f};
+                mg[(w8 * NV + NV - 1) * 64 + l] = ml;
             }
             __syncthreads();
-        };
-        // one step for this wave, whatever its role in it
-        auto do_step = [&](int k, int buf, f32x16& st_cur, f32x16& st_nxt) {
-            if (k < wave_last) {
-                steady_step(k, buf, st_cur, st_nxt);
-            } else if (k == wave_last) {
-                last_step(k, buf, st_cur);
-            } else {   // past this wave's diagonal: keep the ring and the barriers going
-                store_step(buf == 0 ? kNS - 1 : buf - 1);
-                load_step(min(k + 3, n_steps - 1));
-                __syncthreads();
-            }
-        };
-
-        f32x16 st_a, st_b;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) st_a[r] = st_b[r] = 0.0f;
-        if (wave_last >= 0) st_a = score(0);
-        int buf = 0;
-        for (int k = 0; k < n_steps; k += 2) {
-            do_step(k, buf, st_a, st_b);
-            buf = buf == kNS - 1 ? 0 : buf + 1;
-            if (k + 1 < n_steps) do_step(k + 1, buf, st_b, st_a);
-            buf = buf == kNS - 1 ? 0 : buf + 1;
-        }
-
-        // epilogue: O = O^T / l ; register r of tile dt is d = 32 dt + 8 (r/4) + 4 hh + r%4
-        const float inv = 1.0f / half_sum(lsum);
-        if (my_q < S) {
+            const int pw8 = w8 ^ 4;
+            const f32x4 oml = mg[(pw8 * NV + NV - 1) * 64 + l];
+            const float m_all = fmaxf(M, oml[0]);
+            const float a_me = fast_exp2(M - m_all), a_ot = fast_exp2(oml[0] - m_all);
+            const float inv = 1.0f / (L * a_me + oml[1] * a_ot);
+            const float s_me = a_me * inv, s_ot = a_ot * inv;
             const long orow = (((long)b * p.Hq + h) * S + my_q) * (long)D;
 #pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
+            for (int dt = 0; dt < HALF; ++dt)
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
-                    const int d = 32 * dt + 8 * r4 + 4 * hh;
-                    const float x0 = o[dt][4 * r4] * inv, x1 = o[dt][4 * r4 + 1] * inv;
-                    const float x2 = o[dt][4 * r4 + 2] * inv, x3 = o[dt][4 * r4 + 3] * inv;
-                    if (OUT_F32) {
-                        f32x4 ov = {x0, x1, x2, x3};
-                        *reinterpret_cast<f32x4*>((float*)p.out + orow + d) = ov;
-                    } else {
-                        u32x2 ov;
-                        ov[0] = pack_bf16x2(x0, x1);
-                        ov[1] = pack_bf16x2(x2, x3);
-                        *reinterpret_cast<u32x2*>((uint16_t*)p.out + orow + d) = ov;
+                    const f32x4 ot = mg[(pw8 * NV + dt * 4 + r4) * 64 + l];
+                    float xo[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float mine = grp == 0 ? o[dt][4 * r4 + e] : o[HALF + dt][4 * r4 + e];
+                        xo[e] = fmaf(mine, s_me, ot[e] * s_ot);
+                    }
+                    // register r of tile dt is d = 32 dt + 8 (r/4) + 4 hh + r%4
+                    const int d = 32 * (keep0 + dt) + 8 * r4 + 4 * hh;
+                    if (my_q < S) {
+                        if (OUT_F32) {
+                            f32x4 ov = {xo[0], xo[1], xo[2], xo[3]};
+                            *reinterpret_cast<f32x4*>((float*)p.out + orow + d) = ov;
+                        } else {
+                            u32x2 ov;
+                            ov[0] = pack_bf16x2(xo[0], xo[1]);
+                            ov[1] = pack_bf16x2(xo[2], xo[3]);
+                            *reinterpret_cast<u32x2*>((uint16_t*)p.out + orow + d) = ov;
+                        }
                     }
                 }
         }
@@ -500,7 +512,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void slim_prefill_kernel(const 
 
 template <int D, bool KV_I8, bool OUT_F32>
 static hipError_t launch_one(const PrefillParams& p, hipStream_t stream) {
-    const unsigned grid = (unsigned)(8 * (p.single ? p.per_xcd : p.chunk));
+    const unsigned grid = (unsigned)(8 * p.chunk);
     hipLaunchKernelGGL((slim_prefill_kernel<D, KV_I8, OUT_F32>), dim3(grid), dim3(kPrefillThreads), 0,
                        stream, p);
     return hipGetLastError();
@@ -522,11 +534,6 @@ hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream) {
     p.n_pair = (p.n_rb + 1) / 2;
     p.total = a.batch * a.q_heads * p.n_pair;
     p.chunk = (p.total + 7) / 8;
-    // fewer pairs than two workgroups per compute unit (256 CUs): one row block per workgroup
-    const int n_bh = a.batch * a.q_heads;
-    p.single = (p.causal && n_bh % 8 == 0 && p.n_rb > 1 && p.total < 512) ? 1 : 0;
-    p.local_heads = n_bh / 8;
-    p.per_xcd = p.local_heads * p.n_rb;
     p.scale_log2e = a.softmax_scale * kLog2e;
     const int sel = (a.head_dim == 128 ? 4 : 0) | (a.kv_int8 ? 2 : 0) | (a.out_f32 ? 1 : 0);
     switch (sel) {
