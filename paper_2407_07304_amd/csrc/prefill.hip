@@ -23,9 +23,11 @@
 //   - O^T accumulators: lane = query column, so the online-softmax rescale is a per-lane
 //     scalar multiply; the running max is lazy (it moves only when a row's max grew by more
 //     than 2^8), so the rescale runs a few times per row block.
-//   - K/V tiles reach a four-slot LDS ring through registers: all 512 threads load one
-//     16-byte piece per tile two phases before they store it, and a tile is stored two
-//     phases before it is read.
+//   - K/V tiles live in a four-slot LDS ring of unpadded rows whose 16-byte chunks are XOR-
+//     swizzled by the row, so both the 128-bit K row reads and the V transpose reads are
+//     free of bank conflicts.  bf16 tiles are written by the memory pipe itself (buffer
+//     loads with an LDS destination, issued by the group in its matrix phase, five (K) and
+//     three (V) tiles ahead); INT8 tiles pass through registers, where they are widened.
 //   - Under the causal mask a workgroup takes the row-block pair (n-1-x, x) one after the
 //     other, so every workgroup does the same amount of work.
 #include <type_traits>
@@ -77,20 +79,27 @@ template <int D, bool KV_I8, bool OUT_F32>
 __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const PrefillParams p) {
     constexpr int KS = D / 16;       // k-steps of the score MFMA
     constexpr int DT = D / 32;       // 32-row tiles of O^T
-    constexpr int LDKK = D + 8;      // K rows: 16 B of padding, conflict-free 128-bit row reads
-    constexpr int LDKV = D + 32;     // V rows: 64 B of padding, conflict-free transpose reads
     constexpr int ROWB = KV_I8 ? D : 2 * D;   // bytes per K/V row in memory
-    constexpr int CPR = ROWB / 16;            // 16-byte pieces per row
-    constexpr int CH = kBC * CPR;             // pieces per tile and tensor: 512, 256 or 128
-    constexpr int KSLOT = kBC * LDKK, VSLOT = kBC * LDKV;   // elements per ring slot
-    constexpr int K_BYTES = kRing * KSLOT * 2, V_BYTES = kRing * VSLOT * 2;
-    constexpr int NV = DT / 2 * 4 + 1;   // f32x4 vectors a wave hands to its partner at the merge
-    static_assert(8 * NV * 64 * 16 <= K_BYTES + V_BYTES, "merge buffer must fit in the ring");
+    // LDS tile layouts.  bf16 K/V: unpadded rows (that is how the memory pipe writes them), the 16-byte
+    // chunk c of row r at chunk position c ^ swz(r).  K: the 16 rows a 128-bit read touches in one pass
+    // land on 16 different bank groups.  V: the 4 rows x 4 chunks a transpose read touches in one pass do.
+    // INT8 K/V (written from registers): no swizzle, rows padded by 16 bytes (K) and 64 bytes (V) instead,
+    // which keeps every address a base register plus a constant.
+    constexpr int ROWL = 2 * D;               // bytes of data per LDS row
+    constexpr int ROWLK = KV_I8 ? ROWL + 16 : ROWL, ROWLV = KV_I8 ? ROWL + 64 : ROWL;   // row pitch
+    constexpr int TILEBK = kBC * ROWLK, TILEBV = kBC * ROWLV;   // bytes per tile in LDS
+    constexpr int TILEB = TILEBK;             // (bf16: both tensors)
+    constexpr int CPL = ROWL / 16;            // 16-byte chunks per LDS row: 16 or 8
+    constexpr int RPL = 256 / ROWL;           // rows per 256-byte line of banks: 1 or 2
+    constexpr int K_BYTES = kRing * TILEBK, V_BYTES = kRing * TILEBV;
+    constexpr int NV = DT / 2 * 4 + 1;        // f32x4 vectors a wave hands to its partner at the merge
+    constexpr int MERGE_BYTES = 8 * NV * 64 * 16;
+    constexpr int RING_BYTES = K_BYTES + V_BYTES > MERGE_BYTES ? K_BYTES + V_BYTES : MERGE_BYTES;
+    auto swz_k = [](int r) { return KV_I8 ? 0 : (r / RPL) & (CPL - 1); };
+    auto swz_v = [](int r) { return KV_I8 ? 0 : ((r / RPL) & (CPL / 4 - 1)) << 2; };
 
-    __shared__ __attribute__((aligned(16))) char smem[K_BYTES + V_BYTES + kRing * 2 * kBC * 4];
-    uint16_t* const Ks = reinterpret_cast<uint16_t*>(smem);
-    uint16_t* const Vs = reinterpret_cast<uint16_t*>(smem + K_BYTES);
-    float* const scS = reinterpret_cast<float*>(smem + K_BYTES + V_BYTES);   // INT8: per slot [0,32) k_scale*c, [32,64) v_scale
+    __shared__ __attribute__((aligned(16))) char smem[RING_BYTES + kRing * 2 * kBC * 4];
+    float* const scS = reinterpret_cast<float*>(smem + RING_BYTES);   // INT8: per slot [0,32) k_scale*c, [32,64) v_scale
 
     // workgroup -> (batch*head, row-block pair).  Hardware deals workgroup ids round-robin over the 8
     // XCDs, so consecutive virtual ids (which share K/V) are steered to one XCD.
@@ -112,28 +121,71 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
     const int l = tid & 63, l32 = l & 31, hh = l >> 5;
     const long kvrow0 = ((long)b * p.Hkv + g) * (long)S;
 
-    // ---- staging: global -> registers -> LDS ring.  Buffer loads: the descriptor covers exactly this
-    // head's K (V) slab, the offset is a per-thread constant plus the tile offset, and pieces past the
-    // end of the sequence read as zero (those keys are masked in the softmax).
-    const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)((const char*)p.k + kvrow0 * ROWB), 0, (int)((unsigned)S * ROWB), 0x00020000);
-    const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc(
-        (void*)((const char*)p.v + kvrow0 * ROWB), 0, (int)((unsigned)S * ROWB), 0x00020000);
-    const float* sslab = KV_I8 ? ((l < kBC ? p.ks : p.vs) + kvrow0) : nullptr;
-    // A tile (CH 16-byte pieces per tensor) is staged by the four waves of ONE group: piece gl + 256 i of
-    // thread gl.  The last wave of a group also carries the tile's 32 + 32 scales (INT8).
+    // ---- staging.  The buffer descriptors cover exactly this head's K (V) slab: pieces past the end of
+    // the sequence read as zero (those keys are masked in the softmax).  A tile is staged by the four
+    // waves of ONE group.
+    const char* const kslab = (const char*)p.k + kvrow0 * ROWB;
+    const char* const vslab = (const char*)p.v + kvrow0 * ROWB;
+    const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc((void*)kslab, 0, (int)((unsigned)S * ROWB), 0x00020000);
+    const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc((void*)vslab, 0, (int)((unsigned)S * ROWB), 0x00020000);
+
+    // bf16: one buffer load with an LDS destination moves 64 consecutive 16-byte chunk positions (RPW whole
+    // rows); lane i fills position i, so it asks for the chunk the swizzle puts there.  The load is
+    // written as inline assembly on purpose: the compiler then keeps no book on it, and neither its
+    // barriers nor its LDS reads wait for requests that are meant to stay in flight for two phases.
+    // Completion is tracked by hand (vmcnt) where a tile becomes readable.
+    constexpr int RPW = 64 / CPL;              // rows per wave-wide load: 4 or 8
+    constexpr int NLD = kBC / (4 * RPW);       // loads per wave, tile and tensor: 2 or 1
+    auto raw_rsrc = [&](const char* base) {    // the same descriptor as four plain dwords
+        const unsigned long long a64 = (unsigned long long)base;
+        u32x4 d;
+        d[0] = __builtin_amdgcn_readfirstlane((unsigned)a64);
+        d[1] = __builtin_amdgcn_readfirstlane((unsigned)(a64 >> 32) & 0xffffu);
+        d[2] = __builtin_amdgcn_readfirstlane((unsigned)S * ROWB);
+        d[3] = 0x00020000u;
+        return d;
+    };
+    const u32x4 krs_raw = raw_rsrc(kslab), vrs_raw = raw_rsrc(vslab);
+    unsigned d_koff[NLD], d_voff[NLD];
+#pragma unroll
+    for (int j = 0; j < NLD; ++j) {
+        const int r = (kBC / NLD) * j + RPW * w + l / CPL, pos = l % CPL;
+        d_koff[j] = (unsigned)r * ROWB + (unsigned)((pos ^ swz_k(r)) * 16);
+        d_voff[j] = (unsigned)r * ROWB + (unsigned)((pos ^ swz_v(r)) * 16);
+    }
+    const unsigned smem_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
+    auto dma_tile = [&](const u32x4 rs, const unsigned (&off)[NLD], int t, int lds_off) {
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) {
+            const unsigned dst = __builtin_amdgcn_readfirstlane(smem_base + (unsigned)(lds_off + ((kBC / NLD) * j + RPW * w) * ROWL));
+            const unsigned voff = (unsigned)t * (kBC * ROWB) + off[j];
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                         :
+                         : "s"(dst), "v"(voff), "s"(rs)
+                         : "memory", "m0");
+        }
+    };
+
+    // INT8: piece gl + 256 i of thread gl (16 codes) goes through registers and leaves as two bf16 chunks.
+    // The last wave of a group also carries the tile's 32 + 32 scales.
+    constexpr int CPR = ROWB / 16;            // 16-byte pieces per row in memory
+    constexpr int CH = kBC * CPR;             // pieces per tile and tensor
     constexpr int NP = CH >= 256 ? CH / 256 : 1;
     const int gl = tid & 255;
     const bool has_p = CH >= 256 || w < CH / 64;
     const bool has_s = KV_I8 && w == 3;   // lanes 0..31: k_scale of key l, lanes 32..63: v_scale of key l-32
+    const float* sslab = KV_I8 ? ((l < kBC ? p.ks : p.vs) + kvrow0) : nullptr;
     unsigned p_off[NP];
-    int p_kdst[NP], p_vdst[NP];
+    int p_kdst[NP][2], p_vdst[NP][2];
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
         const int pid = gl + 256 * i, row = pid / CPR, col = pid % CPR;
         p_off[i] = (unsigned)row * ROWB + (unsigned)col * 16u;
-        p_kdst[i] = row * LDKK + col * (KV_I8 ? 16 : 8);
-        p_vdst[i] = row * LDKV + col * (KV_I8 ? 16 : 8);
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            p_kdst[i][e] = row * ROWLK + (((2 * col + e) ^ swz_k(row)) * 16);
+            p_vdst[i][e] = K_BYTES + row * ROWLV + (((2 * col + e) ^ swz_v(row)) * 16);
+        }
     }
     auto load_tile = [&](const __amdgpu_buffer_rsrc_t rs, int t, u32x4 (&dst)[NP]) {
         if (has_p) {
@@ -145,24 +197,21 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
     auto load_s = [&](int t, float& dst) {
         if (has_s) dst = sslab[min(t * kBC + l32, S - 1)];
     };
-    auto widen16 = [&](const u32x4 cw, uint16_t* dst) {   // 16 INT8 codes -> 16 bf16 (exact)
-        u32x4 lo, hi;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-            lo[2 * i] = pack_bf16x2(i8_to_f32<0>(cw[i]), i8_to_f32<1>(cw[i]));
-            lo[2 * i + 1] = pack_bf16x2(i8_to_f32<2>(cw[i]), i8_to_f32<3>(cw[i]));
-            hi[2 * i] = pack_bf16x2(i8_to_f32<0>(cw[2 + i]), i8_to_f32<1>(cw[2 + i]));
-            hi[2 * i + 1] = pack_bf16x2(i8_to_f32<2>(cw[2 + i]), i8_to_f32<3>(cw[2 + i]));
-        }
-        *reinterpret_cast<u32x4*>(dst) = lo;
-        *reinterpret_cast<u32x4*>(dst + 8) = hi;
-    };
-    auto store_tile = [&](uint16_t* slot_base, const int (&dsts)[NP], const u32x4 (&src)[NP]) {
+    auto store_tile = [&](int slot_off, const int (&dsts)[NP][2], const u32x4 (&src)[NP]) {   // 16 INT8 codes -> 16 bf16 (exact)
         if (has_p) {
 #pragma unroll
             for (int i = 0; i < NP; ++i) {
-                if (KV_I8) widen16(src[i], slot_base + dsts[i]);
-                else *reinterpret_cast<u32x4*>(slot_base + dsts[i]) = src[i];
+                const u32x4 cw = src[i];
+                u32x4 lo, hi;
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    lo[2 * e] = pack_bf16x2(i8_to_f32<0>(cw[e]), i8_to_f32<1>(cw[e]));
+                    lo[2 * e + 1] = pack_bf16x2(i8_to_f32<2>(cw[e]), i8_to_f32<3>(cw[e]));
+                    hi[2 * e] = pack_bf16x2(i8_to_f32<0>(cw[2 + e]), i8_to_f32<1>(cw[2 + e]));
+                    hi[2 * e + 1] = pack_bf16x2(i8_to_f32<2>(cw[2 + e]), i8_to_f32<3>(cw[2 + e]));
+                }
+                *reinterpret_cast<u32x4*>(smem + slot_off + dsts[i][0]) = lo;
+                *reinterpret_cast<u32x4*>(smem + slot_off + dsts[i][1]) = hi;
             }
         }
     };
@@ -176,8 +225,18 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
 
     bf16x8 qreg[KS];
     f32x16 o[DT];
-    const int ka_off = l32 * LDKK + 8 * hh;                                              // K fragment (row l32)
-    const int va_off = (4 * hh + (l & 15) / 4) * LDKV + 16 * ((l >> 4) & 1) + 4 * (l & 3);   // V transpose read
+    // LDS read addresses (bytes).  K fragment of k-step s: row l32, chunk 2 s + hh.  V transpose read: the
+    // 16 lanes of a group fetch rows k..k+3 (4 lanes per row, 8 bytes each) and lane i of the group
+    // receives column i of those 4 rows; per 32-column tile dt the lane reads chunk 4 dt + 2 b4 + (l&3)/2.
+    int k_addr[KS], v_addr[DT];
+#pragma unroll
+    for (int s2 = 0; s2 < KS; ++s2) k_addr[s2] = l32 * ROWLK + (((2 * s2 + hh) ^ swz_k(l32)) * 16);
+    {
+        const int rv = 4 * hh + ((l & 15) >> 2);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+            v_addr[dt] = K_BYTES + rv * ROWLV + (((4 * dt + 2 * ((l >> 4) & 1) + ((l & 3) >> 1)) ^ swz_v(rv)) * 16) + 8 * (l & 1);
+    }
 
     for (int pass = 0; pass < 2; ++pass) {
         const int rb = pass == 0 ? p.n_rb - 1 - x : x;
@@ -205,11 +264,28 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
             for (int r = 0; r < 16; ++r) o[dt][r] = 0.0f;
         float M = kMasked, lsum = 0.0f;   // running max in scaled (log2) units; per-lane partial row sum
 
-        // ---- prologue: K tiles 0..2 and V tile 0 into the ring (group 0: K 0, V 0; group 1: K 1, K 2), and
-        // into registers the tiles each group stores in its first matrix phase (group 1 in phase 0: K 3,
-        // V 1; group 0 in phase 1: K 4, V 2).  All loads are issued together.
+        // ---- prologue.  In the steady state a group stages in its matrix phase phi: bf16 requests K tile
+        // phi+5 and V tile phi+3 (in LDS by the end of its next matrix phase); INT8 stores K tile phi+3
+        // and V tile phi+1 from registers and loads K tile phi+5, V tile phi+3 into them.  Everything
+        // earlier is staged here, all requests issued together.
         Stage sg;
-        {
+        if constexpr (!KV_I8) {
+            __syncthreads();   // the previous pass has finished with the ring and the merge buffer
+            // all eight ring slots get a tile (zeros past the end of the sequence): whatever a skipped tile
+            // later leaves in place is finite data of this row block, never the previous pass's merge buffer
+            if (grp == 0) {
+                dma_tile(krs_raw, d_koff, 0, 0);
+                dma_tile(krs_raw, d_koff, 2, 2 * TILEB);
+                dma_tile(vrs_raw, d_voff, 0, K_BYTES);
+                dma_tile(vrs_raw, d_voff, 2, K_BYTES + 2 * TILEB);
+            } else {
+                dma_tile(krs_raw, d_koff, 1, TILEB);
+                dma_tile(krs_raw, d_koff, 3, 3 * TILEB);
+                dma_tile(vrs_raw, d_voff, 1, K_BYTES + TILEB);
+                dma_tile(vrs_raw, d_voff, 3, K_BYTES + 3 * TILEB);
+            }
+            __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wave's requests have landed in LDS
+        } else {
             u32x4 pa[NP], pb[NP];
             float s0 = 0.0f, s1 = 0.0f;
             if (grp == 0) {
@@ -227,12 +303,12 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
             load_s(4 - grp, sg.s);
             __syncthreads();   // the previous pass has finished with the ring and the merge buffer
             if (grp == 0) {
-                store_tile(Ks, p_kdst, pa);
-                store_tile(Vs, p_vdst, pb);
+                store_tile(0, p_kdst, pa);
+                store_tile(0, p_vdst, pb);
                 store_s(0, s0);
             } else {
-                store_tile(Ks + KSLOT, p_kdst, pa);
-                store_tile(Ks + 2 * KSLOT, p_kdst, pb);
+                store_tile(TILEBK, p_kdst, pa);
+                store_tile(2 * TILEBK, p_kdst, pb);
                 store_s(1, s0);
                 store_s(2, s1);
             }
@@ -248,17 +324,16 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         s16x4 vfr[2][2 * DT];
         auto fetch_k = [&](auto slot_c) {
             constexpr int slot = decltype(slot_c)::value;
-            const uint16_t* ka = Ks + slot * KSLOT + ka_off;
 #pragma unroll
-            for (int s = 0; s < KS; ++s) kfr[s] = *reinterpret_cast<const bf16x8*>(ka + 16 * s);
+            for (int s = 0; s < KS; ++s) kfr[s] = *reinterpret_cast<const bf16x8*>(smem + k_addr[s] + slot * TILEBK);
         };
         auto fetch_v = [&](auto slot_c, auto u_c) {
             constexpr int slot = decltype(slot_c)::value, u = decltype(u_c)::value;
-            const uint16_t* va = Vs + slot * VSLOT + va_off + 16 * u * LDKV;
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) {
-                vfr[u][2 * dt] = lds_read_tr16(va + 32 * dt);
-                vfr[u][2 * dt + 1] = lds_read_tr16(va + 8 * LDKV + 32 * dt);
+                const char* va = smem + v_addr[dt] + slot * TILEBV + 16 * u * ROWLV;
+                vfr[u][2 * dt] = lds_read_tr16(reinterpret_cast<const uint16_t*>(va));
+                vfr[u][2 * dt + 1] = lds_read_tr16(reinterpret_cast<const uint16_t*>(va + 8 * ROWLV));
             }
         };
         // One score MFMA, S^T[key][query] += sum over d in [16 s, 16 s + 16) of K[key][d] Q[query][d], and one
@@ -277,8 +352,8 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         // softmax of tile t (scores in st, register r of this lane is key 32 t + 8 (r/4) + 4 hh + r%4):
         // probabilities, rounded to bf16, into pw.  `full`: masked tile, recompute the max exactly.
         // The fast path runs unconditionally (its results are dropped for a tile this row group skips) and
-        // shares its block with the LDS reads of the coming matrix phase (K tile t+2, first 16 keys of V
-        // tile t), which are spread between the vector instructions: the wave never waits on a full LDS
+        // shares its block with the LDS reads of the coming matrix phase (K tile t+2 and V tile t), which
+        // are spread between the vector instructions: the wave never waits on a full LDS
         // queue, and the reads have landed when the phase ends.
         auto softmax = [&](auto slot_c, auto kslot_c, int t, const f32x16& st, u32x4 (&pw)[2]) {
             constexpr int slot = decltype(slot_c)::value;
@@ -296,6 +371,7 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
             }
             fetch_k(kslot_c);
             fetch_v(slot_c, int_c<0>{});
+            if (!KV_I8) fetch_v(slot_c, int_c<1>{});   // (INT8 is short of registers: second half in the matrix phase)
             // Fast path: exponentials against the running max as it stands; the lane's partial sum doubles
             // as the overflow check (lazy running max: it only moves when the sum of a lane's 16
             // probabilities exceeds 2^8, so the accumulator is rescaled a few times per row block).
@@ -311,11 +387,12 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
                 }
                 ps = ps0 + ps1;
             }
+            asm volatile("" : "+v"(ps));   // the sum (and with it every exponential) is formed here, whatever follows
             if (KV_I8) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);   // the key scales first
 #pragma unroll
-            for (int i = 0; i < KS + 2 * DT; ++i) {
+            for (int i = 0; i < KS + (KV_I8 ? 2 : 4) * DT; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
-                __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);   // three vector instructions
+                __builtin_amdgcn_sched_group_barrier(0x002, KV_I8 ? 3 : 2, 0);   // two or three vector instructions
             }
             if (t > t_last) {   // tile skipped by this row group: its P V MFMAs run on zeros
 #pragma unroll
@@ -385,16 +462,10 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
             } else {
                 // Matrix phase of tile t = phi - 1: its P V MFMAs and the score MFMAs of tile t + 2, always all
                 // sixteen (a skipped tile has P = 0, unused scores are dropped), alternating so that the score
-                // chain never issues two dependent MFMAs back to back.  Operands are in registers except the
-                // last 16 keys of V tile t, requested first and used from the ninth MFMA on.  The ring traffic
-                // sits in the shadow of the MFMAs: the pieces loaded two phases ago go to K tile phi+3 and V
-                // tile phi+1 after the first eight, the pieces of K tile phi+5 and V tile phi+3 are requested
-                // after the last one.
-                if (phi > 0) {
-                    fetch_v(int_c<(P4 + 3) & 3>{}, int_c<1>{});
-                } else {   // no tile -1: nothing but zeros may meet the (zero) probabilities
-#pragma unroll
-                    for (int i = 0; i < 2 * DT; ++i) vfr[1][i] = s16x4{0, 0, 0, 0};
+                // chain never issues two dependent MFMAs back to back.  All operands are in registers.  The
+                // ring traffic is issued in the shadow of the MFMAs.
+                if constexpr (KV_I8) {
+                    if (phi > 0) fetch_v(int_c<(P4 + 3) & 3>{}, int_c<1>{});   // last 16 keys of V tile t
                 }
                 f32x16 acc;
 #pragma unroll
@@ -407,9 +478,24 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
                     pv_mfma(0, i, pw);
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                store_tile(Ks + ((P4 + 3) & 3) * KSLOT, p_kdst, sg.k);
-                store_tile(Vs + ((P4 + 1) & 3) * VSLOT, p_vdst, sg.v);
-                store_s((P4 + 3) & 3, sg.s);
+                int in_flight = 0;   // wave-wide requests of this phase still allowed in flight at its end
+                if constexpr (!KV_I8) {
+                    // K tile phi+5 and V tile phi+3 straight into their ring slots; tiles past the last one
+                    // this row block needs are not requested, so the ring is quiet when the pass ends
+                    if (phi + 5 < n_tiles) {
+                        dma_tile(krs_raw, d_koff, phi + 5, ((P4 + 1) & 3) * TILEB);
+                        in_flight += NLD;
+                    }
+                    if (phi > 0 && phi + 3 < n_tiles) {   // (V tile 3 came with the prologue)
+                        dma_tile(vrs_raw, d_voff, phi + 3, K_BYTES + ((P4 + 3) & 3) * TILEB);
+                        in_flight += NLD;
+                    }
+                } else {
+                    // the pieces loaded two phases ago go to K tile phi+3 and V tile phi+1
+                    store_tile(((P4 + 3) & 3) * TILEBK, p_kdst, sg.k);
+                    store_tile(((P4 + 1) & 3) * TILEBV, p_vdst, sg.v);
+                    store_s((P4 + 3) & 3, sg.s);
+                }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int i = 0; i < DT; ++i) {
@@ -419,17 +505,31 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 st = acc;
-                load_tile(krs, phi + 5, sg.k);
-                load_tile(vrs, phi + 3, sg.v);
-                load_s(phi + 5, sg.s);
+                if constexpr (!KV_I8) {
+                    // what this wave requested in its previous matrix phase is read from the next phase on
+                    if (in_flight == 2 * NLD) __builtin_amdgcn_s_waitcnt(0x0f70 | (2 * NLD));
+                    else if (in_flight == NLD) __builtin_amdgcn_s_waitcnt(0x0f70 | NLD);
+                    else __builtin_amdgcn_s_waitcnt(0x0f70);
+                } else {
+                    load_tile(krs, phi + 5, sg.k);
+                    load_tile(vrs, phi + 3, sg.v);
+                    load_s(phi + 5, sg.s);
+                }
             }
+            // End of phase: this wave's LDS reads and writes are done, then the workgroup barrier.  (Not
+            // __syncthreads(): its fence would also wait for the buffer loads just sent towards LDS.  The
+            // empty statements keep the compiler from moving memory accesses across.)
             __builtin_amdgcn_sched_barrier(0);
-            __syncthreads();
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
             __builtin_amdgcn_sched_barrier(0);
         };
         auto run = [&](auto grp_c) {
             constexpr int G = decltype(grp_c)::value;
-            // group 0 starts with the scores of tile 0; group 1 computes those of tile 1 in phase 0
+            // group 0 starts with the scores of tile 0; group 1 computes those of tile 1 in phase 0, which has
+            // no tile -1: nothing but zeros may meet its (zero) probabilities
             if (G == 0) {
                 fetch_k(int_c<0>{});
 #pragma unroll
@@ -439,7 +539,14 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
             } else {
                 fetch_k(int_c<1>{});
 #pragma unroll
-                for (int i = 0; i < 2 * DT; ++i) vfr[0][i] = s16x4{0, 0, 0, 0};   // phase 0 has no tile -1
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int i = 0; i < 2 * DT; ++i) vfr[u][i] = s16x4{0, 0, 0, 0};
+            }
+            if constexpr (!KV_I8) {
+                // K tile 4 takes the slot of K tile 0 once every wave of group 0 has read that
+                __syncthreads();
+                if (G == 1 && 4 < n_tiles) dma_tile(krs_raw, d_koff, 4, 0);
             }
             for (int phi = 0; phi <= last_phase; phi += 4) {
                 phase(int_c<0>{}, grp_c, phi);
@@ -456,7 +563,7 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         // ---- merge the two groups' partial results.  A wave keeps half of its O^T tiles and hands the
         // other half, with its max and row sum, to its partner (same rows, other group) through LDS.
         {
-            f32x4* mg = reinterpret_cast<f32x4*>(smem);   // [wave][NV][lane]; the ring is dead after the last barrier
+            f32x4* mg = reinterpret_cast<f32x4*>(smem);   // [wave][NV][lane]; the ring is dead and quiet after the last barrier
             const float L = half_sum(lsum);
             constexpr int HALF = DT / 2;
             const int keep0 = grp == 0 ? 0 : HALF;
