@@ -94,12 +94,12 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
     constexpr int K_BYTES = kRing * TILEBK, V_BYTES = kRing * TILEBV;
     constexpr int NV = DT / 2 * 4 + 1;        // f32x4 vectors a wave hands to its partner at the merge
     constexpr int MERGE_BYTES = 8 * NV * 64 * 16;
-    constexpr int RING_BYTES = K_BYTES + V_BYTES > MERGE_BYTES ? K_BYTES + V_BYTES : MERGE_BYTES;
+    constexpr int RING_BYTES = K_BYTES + V_BYTES;   // the merge buffer has room of its own: tiles of the next pass land in the ring meanwhile
     auto swz_k = [](int r) { return KV_I8 ? 0 : (r / RPL) & (CPL - 1); };
     auto swz_v = [](int r) { return KV_I8 ? 0 : ((r / RPL) & (CPL / 4 - 1)) << 2; };
 
-    __shared__ __attribute__((aligned(16))) char smem[RING_BYTES + kRing * 2 * kBC * 4];
-    float* const scS = reinterpret_cast<float*>(smem + RING_BYTES);   // INT8: per slot [0,32) k_scale*c, [32,64) v_scale
+    __shared__ __attribute__((aligned(16))) char smem[RING_BYTES + MERGE_BYTES + kRing * 2 * kBC * 4];
+    float* const scS = reinterpret_cast<float*>(smem + RING_BYTES + MERGE_BYTES);   // INT8: per slot [0,32) k_scale*c, [32,64) v_scale
 
     // workgroup -> (batch*head, row-block pair).  Hardware deals workgroup ids round-robin over the 8
     // XCDs, so consecutive virtual ids (which share K/V) are steered to one XCD.
@@ -238,9 +238,18 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
             v_addr[dt] = K_BYTES + rv * ROWLV + (((4 * dt + 2 * ((l >> 4) & 1) + ((l & 3) >> 1)) ^ swz_v(rv)) * 16) + 8 * (l & 1);
     }
 
+    // Q^T B-operands of a row block: lane holds row my_q, d = 16 s + 8 hh + [0,8)
+    auto load_q = [&](int rb_q) {
+        const int q_row = min(rb_q * kBR + 32 * w + l32, S - 1);
+        const uint16_t* qp = p.q + (((long)b * p.Hq + h) * S + q_row) * (long)D + 8 * hh;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) qreg[s] = *reinterpret_cast<const bf16x8*>(qp + 16 * s);
+    };
+    bool continued = false;   // the first K/V tiles of this pass were requested by the previous one
     for (int pass = 0; pass < 2; ++pass) {
         const int rb = pass == 0 ? p.n_rb - 1 - x : x;
         if (pass == 1 && rb == p.n_rb - 1 - x) break;   // the middle row block of an odd count
+        const bool has_next = pass == 0 && x != p.n_rb - 1 - x;
         const int i0 = rb * kBR;
         const int my_q = i0 + 32 * w + l32;             // this lane's query row (may be >= S in the last block)
         const int wave_q_lo = i0 + 32 * w;
@@ -252,12 +261,11 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         const int t_last = wave_q_lo >= S ? -1 : (p.causal ? min(n_tiles - 1, wave_q_lo / kBC) : n_tiles - 1);
         const int lim = p.causal ? min(my_q, S - 1) : S - 1;   // last key this lane's row may see
 
-        // Q^T B-operands: lane holds row my_q, d = 16 s + 8 hh + [0,8)
-        {
-            const uint16_t* qp = p.q + (((long)b * p.Hq + h) * S + min(my_q, S - 1)) * (long)D + 8 * hh;
-#pragma unroll
-            for (int s = 0; s < KS; ++s) qreg[s] = *reinterpret_cast<const bf16x8*>(qp + 16 * s);
-        }
+        if (pass == 0) load_q(rb);   // (the second pass's Q is requested before the first one's merge)
+        // bf16: the ring keeps turning over the pass boundary.  The second pass reads the same head's K/V
+        // from tile 0 again, so the last matrix phases of this pass already request its tiles 0..3 into
+        // the slots they belong to (the tile count must be a multiple of the ring depth for that).
+        const bool cont = !KV_I8 && has_next && n_tiles % kRing == 0 && n_tiles >= 2 * kRing;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -270,7 +278,7 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         // earlier is staged here, all requests issued together.
         Stage sg;
         if constexpr (!KV_I8) {
-            __syncthreads();   // the previous pass has finished with the ring and the merge buffer
+            if (!continued) {
             // all eight ring slots get a tile (zeros past the end of the sequence): whatever a skipped tile
             // later leaves in place is finite data of this row block, never the previous pass's merge buffer
             if (grp == 0) {
@@ -283,6 +291,7 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
                 dma_tile(krs_raw, d_koff, 3, 3 * TILEB);
                 dma_tile(vrs_raw, d_voff, 1, K_BYTES + TILEB);
                 dma_tile(vrs_raw, d_voff, 3, K_BYTES + 3 * TILEB);
+            }
             }
             __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wave's requests have landed in LDS
         } else {
@@ -301,7 +310,6 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
             load_tile(krs, 4 - grp, sg.k);
             load_tile(vrs, 2 - grp, sg.v);
             load_s(4 - grp, sg.s);
-            __syncthreads();   // the previous pass has finished with the ring and the merge buffer
             if (grp == 0) {
                 store_tile(0, p_kdst, pa);
                 store_tile(0, p_vdst, pb);
@@ -481,13 +489,15 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
                 int in_flight = 0;   // wave-wide requests of this phase still allowed in flight at its end
                 if constexpr (!KV_I8) {
                     // K tile phi+5 and V tile phi+3 straight into their ring slots; tiles past the last one
-                    // this row block needs are not requested, so the ring is quiet when the pass ends
-                    if (phi + 5 < n_tiles) {
-                        dma_tile(krs_raw, d_koff, phi + 5, ((P4 + 1) & 3) * TILEB);
+                    // this row block needs are not requested
+                    // (past the end of a pass that continues: tiles 0..3 of the next one)
+                    const int kt = phi + 5, vt = phi + 3, n_req = cont ? n_tiles + kRing : n_tiles;
+                    if (kt < n_req) {
+                        dma_tile(krs_raw, d_koff, kt < n_tiles ? kt : kt - n_tiles, ((P4 + 1) & 3) * TILEB);
                         in_flight += NLD;
                     }
-                    if (phi > 0 && phi + 3 < n_tiles) {   // (V tile 3 came with the prologue)
-                        dma_tile(vrs_raw, d_voff, phi + 3, K_BYTES + ((P4 + 3) & 3) * TILEB);
+                    if (phi > 0 && vt < n_req) {   // (V tile 3 came with the prologue)
+                        dma_tile(vrs_raw, d_voff, vt < n_tiles ? vt : vt - n_tiles, K_BYTES + ((P4 + 3) & 3) * TILEB);
                         in_flight += NLD;
                     }
                 } else {
@@ -559,11 +569,13 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         };
         if (grp == 0) run(int_c<0>{});
         else run(int_c<1>{});
+        if (has_next) load_q(x);   // in flight during the merge
+        continued = cont;
 
         // ---- merge the two groups' partial results.  A wave keeps half of its O^T tiles and hands the
         // other half, with its max and row sum, to its partner (same rows, other group) through LDS.
         {
-            f32x4* mg = reinterpret_cast<f32x4*>(smem);   // [wave][NV][lane]; the ring is dead and quiet after the last barrier
+            f32x4* mg = reinterpret_cast<f32x4*>(smem + RING_BYTES);   // [wave][NV][lane]
             const float L = half_sum(lsum);
             constexpr int HALF = DT / 2;
             const int keep0 = grp == 0 ? 0 : HALF;

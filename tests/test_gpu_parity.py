@@ -97,6 +97,9 @@ SMALL = [
     # B, Hq, Hkv, S, D
     (1, 2, 2, 1, 128), (1, 2, 1, 5, 64), (2, 4, 2, 127, 128), (1, 2, 2, 128, 64), (1, 4, 1, 129, 128),
     (1, 2, 2, 200, 128), (2, 3, 3, 333, 64), (1, 8, 2, 640, 128), (1, 2, 2, 1000, 64),
+    # two, three and nine row blocks: row-block pairs, a lone middle block, K/V tiles of the second block of a
+    # pair requested while the first one finishes; 96 keys: fewer tiles than ring slots
+    (1, 2, 2, 256, 128), (1, 2, 1, 384, 64), (1, 1, 1, 1152, 128), (1, 2, 2, 96, 128), (1, 1, 1, 1120, 64),
 ]
 
 
