@@ -379,7 +379,8 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
             }
             fetch_k(kslot_c);
             fetch_v(slot_c, int_c<0>{});
-            if (!KV_I8) fetch_v(slot_c, int_c<1>{});   // (INT8 is short of registers: second half in the matrix phase)
+            if (!KV_I8) fetch_v(slot_c, int_c<1>{});   // (INT8 is short of registers: second half in the matrix phase,
+            else __builtin_amdgcn_sched_barrier(0);    //  and its reads all go first)
             // Fast path: exponentials against the running max as it stands; the lane's partial sum doubles
             // as the overflow check (lazy running max: it only moves when the sum of a lane's 16
             // probabilities exceeds 2^8, so the accumulator is rescaled a few times per row block).
@@ -396,11 +397,12 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
                 ps = ps0 + ps1;
             }
             asm volatile("" : "+v"(ps));   // the sum (and with it every exponential) is formed here, whatever follows
-            if (KV_I8) __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);   // the key scales first
+            if (!KV_I8) {
 #pragma unroll
-            for (int i = 0; i < KS + (KV_I8 ? 2 : 4) * DT; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
-                __builtin_amdgcn_sched_group_barrier(0x002, KV_I8 ? 3 : 2, 0);   // two or three vector instructions
+                for (int i = 0; i < KS + 4 * DT; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
+                    __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   // two vector instructions
+                }
             }
             if (t > t_last) {   // tile skipped by this row group: its P V MFMAs run on zeros
 #pragma unroll
@@ -412,11 +414,11 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
             const bool full = t == t_last;   // masked tile: recompute the max exactly
             const bool redo = full || __builtin_amdgcn_ballot_w64(ps > 256.0f) != 0;
             if (redo) {
-                const int key0 = t * kBC + 4 * hh;
+                const int rel = full ? lim - (t * kBC + 4 * hh) : kBC;   // keys of this lane up to offset rel are visible
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
                     const float u = st[r] * cf[r];
-                    a[r] = (!full || key0 + 8 * (r / 4) + (r % 4) <= lim) ? u : kMasked;
+                    a[r] = (8 * (r / 4) + (r % 4) <= rel) ? u : kMasked;
                 }
                 float umax = fmaxf(a[0], a[1]);
 #pragma unroll
