@@ -8,7 +8,8 @@ LIB = os.path.join(HERE, "libslimattn.so")
 SOURCES = ["api.hip", "kv_quant.hip", "decode.hip", "prefill.hip"]
 # prefill.hip: MFMA results stay in arch VGPRs (no AGPR copies around the softmax), and fmaxf needs no
 # NaN quieting (NaN inputs are documented as undefined).  The quantiser keeps the IEEE defaults.
-EXTRA = {"prefill.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form", "-fno-honor-nans", "-mno-amdgpu-ieee"]}
+# -Wno-inline-asm: its buffer loads with an LDS destination set M0 themselves and say so in the clobber list.
+EXTRA = {"prefill.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form", "-fno-honor-nans", "-mno-amdgpu-ieee", "-Wno-inline-asm"]}
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # Packed-fp32 instructions are switched off for every kernel of this library.
