@@ -23,11 +23,15 @@
 //   - O^T accumulators: lane = query column, so the online-softmax rescale is a per-lane
 //     scalar multiply; the running max is lazy (it moves only when a row's max grew by more
 //     than 2^8), so the rescale runs a few times per row block.
-//   - K/V tiles live in a four-slot LDS ring of unpadded rows whose 16-byte chunks are XOR-
-//     swizzled by the row, so both the 128-bit K row reads and the V transpose reads are
-//     free of bank conflicts.  bf16 tiles are written by the memory pipe itself (buffer
-//     loads with an LDS destination, issued by the group in its matrix phase, five (K) and
-//     three (V) tiles ahead); INT8 tiles pass through registers, where they are widened.
+//   - K/V tiles live in an LDS ring (eight K slots, four V slots).  bf16 tiles are written by the
+//     memory pipe itself (buffer loads with an LDS destination, issued by the group in its
+//     matrix phase, six (K) and four (V) tiles ahead) as unpadded rows whose 16-byte chunks are
+//     XOR-swizzled by the row, so both the 128-bit K row reads and the V transpose reads are
+//     free of bank conflicts; INT8 tiles pass through registers, where they are widened, into
+//     padded rows.
+//   - A wave reads its MFMA operands from LDS one matrix phase ahead, each fragment right after
+//     the MFMA that consumed its predecessor: the reads issue in the shadow of the MFMAs and
+//     the softmax phase is pure vector work.
 //   - Under the causal mask a workgroup takes the row-block pair (n-1-x, x) one after the
 //     other, so every workgroup does the same amount of work.
 #include <type_traits>
@@ -39,7 +43,8 @@ namespace slim {
 
 constexpr int kBR = 128;   // query rows per row block (4 row groups x 32)
 constexpr int kBC = 32;    // keys per tile
-constexpr int kRing = 4;   // LDS ring depth (tiles)
+constexpr int kRingK = 8;  // LDS ring depth, K tiles
+constexpr int kRingV = 4;  // LDS ring depth, V tiles
 constexpr int kPrefillThreads = 512;
 
 struct PrefillParams {
@@ -91,15 +96,16 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
     constexpr int TILEB = TILEBK;             // (bf16: both tensors)
     constexpr int CPL = ROWL / 16;            // 16-byte chunks per LDS row: 16 or 8
     constexpr int RPL = 256 / ROWL;           // rows per 256-byte line of banks: 1 or 2
-    constexpr int K_BYTES = kRing * TILEBK, V_BYTES = kRing * TILEBV;
+    constexpr int K_BYTES = kRingK * TILEBK, V_BYTES = kRingV * TILEBV;
     constexpr int NV = DT / 2 * 4 + 1;        // f32x4 vectors a wave hands to its partner at the merge
     constexpr int MERGE_BYTES = 8 * NV * 64 * 16;
-    constexpr int RING_BYTES = K_BYTES + V_BYTES;   // the merge buffer has room of its own: tiles of the next pass land in the ring meanwhile
+    // (the merge buffer takes the place of the ring, which is quiet by then)
+    constexpr int RING_BYTES = K_BYTES + V_BYTES > MERGE_BYTES ? K_BYTES + V_BYTES : MERGE_BYTES;
     auto swz_k = [](int r) { return KV_I8 ? 0 : (r / RPL) & (CPL - 1); };
     auto swz_v = [](int r) { return KV_I8 ? 0 : ((r / RPL) & (CPL / 4 - 1)) << 2; };
 
-    __shared__ __attribute__((aligned(16))) char smem[RING_BYTES + MERGE_BYTES + kRing * 2 * kBC * 4];
-    float* const scS = reinterpret_cast<float*>(smem + RING_BYTES + MERGE_BYTES);   // INT8: per slot [0,32) k_scale*c, [32,64) v_scale
+    __shared__ __attribute__((aligned(16))) char smem[RING_BYTES + kRingK * 2 * kBC * 4];
+    float* const scS = reinterpret_cast<float*>(smem + RING_BYTES);   // INT8: per slot [0,32) k_scale*c, [32,64) v_scale
 
     // workgroup -> (batch*head, row-block pair).  Hardware deals workgroup ids round-robin over the 8
     // XCDs, so consecutive virtual ids (which share K/V) are steered to one XCD.
@@ -245,7 +251,6 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
 #pragma unroll
         for (int s = 0; s < KS; ++s) qreg[s] = *reinterpret_cast<const bf16x8*>(qp + 16 * s);
     };
-    bool continued = false;   // the first K/V tiles of this pass were requested by the previous one
     for (int pass = 0; pass < 2; ++pass) {
         const int rb = pass == 0 ? p.n_rb - 1 - x : x;
         if (pass == 1 && rb == p.n_rb - 1 - x) break;   // the middle row block of an odd count
@@ -262,10 +267,6 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         const int lim = p.causal ? min(my_q, S - 1) : S - 1;   // last key this lane's row may see
 
         if (pass == 0) load_q(rb);   // (the second pass's Q is requested before the first one's merge)
-        // bf16: the ring keeps turning over the pass boundary.  The second pass reads the same head's K/V
-        // from tile 0 again, so the last matrix phases of this pass already request its tiles 0..3 into
-        // the slots they belong to (the tile count must be a multiple of the ring depth for that).
-        const bool cont = !KV_I8 && has_next && n_tiles % kRing == 0 && n_tiles >= 2 * kRing;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -273,76 +274,72 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         float M = kMasked, lsum = 0.0f;   // running max in scaled (log2) units; per-lane partial row sum
 
         // ---- prologue.  In the steady state a group stages in its matrix phase phi: bf16 requests K tile
-        // phi+5 and V tile phi+3 (in LDS by the end of its next matrix phase); INT8 stores K tile phi+3
-        // and V tile phi+1 from registers and loads K tile phi+5, V tile phi+3 into them.  Everything
-        // earlier is staged here, all requests issued together.
+        // phi+6 and V tile phi+4 (in LDS by the end of its next matrix phase); INT8 stores K tile phi+5
+        // and V tile phi+3 from registers and loads K tile phi+7, V tile phi+5 into them.  Everything
+        // earlier is staged here, all requests issued together.  Every V slot gets a tile (zeros past the
+        // end of the sequence): whatever a skipped tile later leaves in place is finite data of this row
+        // block, never the previous pass's merge buffer.
         Stage sg;
+        __syncthreads();   // the previous pass has finished with the merge buffer, which lies over the ring
         if constexpr (!KV_I8) {
-            if (!continued) {
-            // all eight ring slots get a tile (zeros past the end of the sequence): whatever a skipped tile
-            // later leaves in place is finite data of this row block, never the previous pass's merge buffer
             if (grp == 0) {
                 dma_tile(krs_raw, d_koff, 0, 0);
                 dma_tile(krs_raw, d_koff, 2, 2 * TILEB);
+                dma_tile(krs_raw, d_koff, 4, 4 * TILEB);
                 dma_tile(vrs_raw, d_voff, 0, K_BYTES);
                 dma_tile(vrs_raw, d_voff, 2, K_BYTES + 2 * TILEB);
             } else {
                 dma_tile(krs_raw, d_koff, 1, TILEB);
                 dma_tile(krs_raw, d_koff, 3, 3 * TILEB);
+                dma_tile(krs_raw, d_koff, 5, 5 * TILEB);
                 dma_tile(vrs_raw, d_voff, 1, K_BYTES + TILEB);
                 dma_tile(vrs_raw, d_voff, 3, K_BYTES + 3 * TILEB);
             }
-            }
             __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wave's requests have landed in LDS
         } else {
-            u32x4 pa[NP], pb[NP];
-            float s0 = 0.0f, s1 = 0.0f;
+            // LDS: K tiles 0..4, V tiles 0..2 (group 0: K 0, 2, 4, V 0, 2; group 1: K 1, 3, V 1); registers: what
+            // each group stores in its first matrix phase (group 1 in phase 0: K 5, V 3; group 0 in phase 1: K 6, V 4)
+            u32x4 ta[NP], tb[NP], tc[NP], td[NP], te[NP];
+            float sa = 0.0f, sb = 0.0f, sc3 = 0.0f;
+            load_tile(krs, grp, ta);
+            load_tile(krs, 2 + grp, tb);
+            load_tile(vrs, grp, td);
+            load_s(grp, sa);
+            load_s(2 + grp, sb);
             if (grp == 0) {
-                load_tile(krs, 0, pa);
-                load_tile(vrs, 0, pb);
-                load_s(0, s0);
-            } else {
-                load_tile(krs, 1, pa);
-                load_tile(krs, 2, pb);
-                load_s(1, s0);
-                load_s(2, s1);
+                load_tile(krs, 4, tc);
+                load_tile(vrs, 2, te);
+                load_s(4, sc3);
             }
-            load_tile(krs, 4 - grp, sg.k);
-            load_tile(vrs, 2 - grp, sg.v);
-            load_s(4 - grp, sg.s);
+            load_tile(krs, 6 - grp, sg.k);
+            load_tile(vrs, 4 - grp, sg.v);
+            load_s(6 - grp, sg.s);
+            store_tile(grp * TILEBK, p_kdst, ta);
+            store_tile((2 + grp) * TILEBK, p_kdst, tb);
+            store_tile(grp * TILEBV, p_vdst, td);
+            store_s(grp, sa);
+            store_s(2 + grp, sb);
             if (grp == 0) {
-                store_tile(0, p_kdst, pa);
-                store_tile(0, p_vdst, pb);
-                store_s(0, s0);
-            } else {
-                store_tile(TILEBK, p_kdst, pa);
-                store_tile(2 * TILEBK, p_kdst, pb);
-                store_s(1, s0);
-                store_s(2, s1);
+                store_tile(4 * TILEBK, p_kdst, tc);
+                store_tile(2 * TILEBV, p_vdst, te);
+                store_s(4, sc3);
             }
         }
         __syncthreads();
 
-        // Operand fragments are fetched from LDS one phase ahead (by the wave's own softmax phase, which
-        // leaves the LDS pipe idle), so the matrix phase starts with its operands in registers:
+        // Operand fragments, read from LDS one matrix phase ahead:
         //   kfr: K tile as A operand, lane = key l32, d = 16 s + 8 hh + [0,8)
         //   vfr[u]: V^T tile as A operand for keys 16u..16u+15.  Transpose read: the 16 lanes of a group
         //   fetch rows k..k+3 (4 lanes per row, 4 columns each) and lane i receives column i of those rows.
         bf16x8 kfr[KS];
         s16x4 vfr[2][2 * DT];
-        auto fetch_k = [&](auto slot_c) {
-            constexpr int slot = decltype(slot_c)::value;
-#pragma unroll
-            for (int s = 0; s < KS; ++s) kfr[s] = *reinterpret_cast<const bf16x8*>(smem + k_addr[s] + slot * TILEBK);
+        auto fetch_k1 = [&](int s, int slot_off) {   // slot_off: byte offset of the K ring slot
+            kfr[s] = *reinterpret_cast<const bf16x8*>(smem + k_addr[s] + slot_off);
         };
-        auto fetch_v = [&](auto slot_c, auto u_c) {
-            constexpr int slot = decltype(slot_c)::value, u = decltype(u_c)::value;
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt) {
-                const char* va = smem + v_addr[dt] + slot * TILEBV + 16 * u * ROWLV;
-                vfr[u][2 * dt] = lds_read_tr16(reinterpret_cast<const uint16_t*>(va));
-                vfr[u][2 * dt + 1] = lds_read_tr16(reinterpret_cast<const uint16_t*>(va + 8 * ROWLV));
-            }
+        auto fetch_v1 = [&](int u, int dt, int slot_off) {   // slot_off: byte offset of the V ring slot
+            const char* va = smem + v_addr[dt] + slot_off + 16 * u * ROWLV;
+            vfr[u][2 * dt] = lds_read_tr16(reinterpret_cast<const uint16_t*>(va));
+            vfr[u][2 * dt + 1] = lds_read_tr16(reinterpret_cast<const uint16_t*>(va + 8 * ROWLV));
         };
         // One score MFMA, S^T[key][query] += sum over d in [16 s, 16 s + 16) of K[key][d] Q[query][d], and one
         // P V MFMA, O^T[d][query] += sum_key V[key][d] P[query][key] for d in [32 dt, 32 dt + 32); k-step u of
@@ -358,18 +355,20 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
             o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb, o[dt], 0, 0, 0);
         };
         // softmax of tile t (scores in st, register r of this lane is key 32 t + 8 (r/4) + 4 hh + r%4):
-        // probabilities, rounded to bf16, into pw.  `full`: masked tile, recompute the max exactly.
-        // The fast path runs unconditionally (its results are dropped for a tile this row group skips) and
-        // shares its block with the LDS reads of the coming matrix phase (K tile t+2 and V tile t), which
-        // are spread between the vector instructions: the wave never waits on a full LDS
-        // queue, and the reads have landed when the phase ends.
-        auto softmax = [&](auto slot_c, auto kslot_c, int t, const f32x16& st, u32x4 (&pw)[2]) {
-            constexpr int slot = decltype(slot_c)::value;
+        // probabilities, rounded to bf16, into pw.  Pure vector work.
+        auto softmax = [&](int sc_slot, int t, const f32x16& st, u32x4 (&pw)[2]) {
+            if (t > t_last) {   // tile skipped by this row group: its P V MFMAs run on zeros
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) pw[u][i] = 0u;
+                return;
+            }
             float cf[16];
             if (KV_I8) {
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
-                    const f32x4 kf = *reinterpret_cast<const f32x4*>(&scS[slot * (2 * kBC) + 8 * r4 + 4 * hh]);
+                    const f32x4 kf = *reinterpret_cast<const f32x4*>(&scS[sc_slot * (2 * kBC) + 8 * r4 + 4 * hh]);
 #pragma unroll
                     for (int e = 0; e < 4; ++e) cf[4 * r4 + e] = kf[e];
                 }
@@ -377,15 +376,13 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
 #pragma unroll
                 for (int r = 0; r < 16; ++r) cf[r] = c;
             }
-            fetch_k(kslot_c);
-            fetch_v(slot_c, int_c<0>{});
-            if (!KV_I8) fetch_v(slot_c, int_c<1>{});   // (INT8 is short of registers: second half in the matrix phase,
-            else __builtin_amdgcn_sched_barrier(0);    //  and its reads all go first)
             // Fast path: exponentials against the running max as it stands; the lane's partial sum doubles
             // as the overflow check (lazy running max: it only moves when the sum of a lane's 16
             // probabilities exceeds 2^8, so the accumulator is rescaled a few times per row block).
-            float a[16], ps;
-            {
+            const bool full = t == t_last;   // masked tile: recompute the max exactly
+            float a[16], ps = 0.0f;
+            bool redo = full;
+            if (!full) {
                 float ps0 = 0.0f, ps1 = 0.0f;
 #pragma unroll
                 for (int r = 0; r < 16; r += 2) {
@@ -395,24 +392,8 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
                     ps1 += a[r + 1];
                 }
                 ps = ps0 + ps1;
+                redo = __builtin_amdgcn_ballot_w64(ps > 256.0f) != 0;
             }
-            asm volatile("" : "+v"(ps));   // the sum (and with it every exponential) is formed here, whatever follows
-            if (!KV_I8) {
-#pragma unroll
-                for (int i = 0; i < KS + 4 * DT; ++i) {
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // one LDS read
-                    __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);   // two vector instructions
-                }
-            }
-            if (t > t_last) {   // tile skipped by this row group: its P V MFMAs run on zeros
-#pragma unroll
-                for (int u = 0; u < 2; ++u)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) pw[u][i] = 0u;
-                return;
-            }
-            const bool full = t == t_last;   // masked tile: recompute the max exactly
-            const bool redo = full || __builtin_amdgcn_ballot_w64(ps > 256.0f) != 0;
             if (redo) {
                 const int rel = full ? lim - (t * kBC + 4 * hh) : kBC;   // keys of this lane up to offset rel are visible
 #pragma unroll
@@ -446,7 +427,7 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
                 // the probabilities take their token's v_scale before they are rounded to bf16
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
-                    const f32x4 vf = *reinterpret_cast<const f32x4*>(&scS[slot * (2 * kBC) + kBC + 8 * r4 + 4 * hh]);
+                    const f32x4 vf = *reinterpret_cast<const f32x4*>(&scS[sc_slot * (2 * kBC) + kBC + 8 * r4 + 4 * hh]);
 #pragma unroll
                     for (int e = 0; e < 4; ++e) a[4 * r4 + e] *= vf[e];
                 }
@@ -463,69 +444,80 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         u32x4 pw[2] = {{0u, 0u, 0u, 0u}, {0u, 0u, 0u, 0u}};
 
         // One phase.  The group whose parity matches the phase does the softmax of tile phi; the other one
-        // does the matrix work of tile phi-1 (P V, and the scores of tile phi+1) and the ring traffic.
+        // does the matrix work of tile phi-1 (P V, and the scores of tile phi+1), reads the operands of its
+        // next matrix phase and moves the ring on.
         auto phase = [&](auto p4_c, auto grp_c, int phi) {
             constexpr int P4 = decltype(p4_c)::value, G = decltype(grp_c)::value;
             if constexpr ((P4 & 1) == G) {
-                const int t = phi;
-                softmax(int_c<P4>{}, int_c<(P4 + 2) & 3>{}, t, st, pw);
+                softmax(phi & (kRingK - 1), phi, st, pw);
             } else {
                 // Matrix phase of tile t = phi - 1: its P V MFMAs and the score MFMAs of tile t + 2, always all
                 // sixteen (a skipped tile has P = 0, unused scores are dropped), alternating so that the score
-                // chain never issues two dependent MFMAs back to back.  All operands are in registers.  The
-                // ring traffic is issued in the shadow of the MFMAs.
-                if constexpr (KV_I8) {
-                    if (phi > 0) fetch_v(int_c<(P4 + 3) & 3>{}, int_c<1>{});   // last 16 keys of V tile t
-                }
+                // chain never issues two dependent MFMAs back to back.  Every operand fragment is refilled
+                // right after the MFMA that consumed it, with the fragment the next matrix phase of this wave
+                // needs (K tile phi+3, V tile phi+1): the LDS reads, and the ring traffic, are issued in the
+                // shadow of the MFMAs.  (The fences keep the issue order as written.)
+                const int k_rd = ((phi + 3) & (kRingK - 1)) * TILEBK;
+                constexpr int v_rd = ((P4 + 1) & 3) * TILEBV;
+                // the wave that feeds the matrix pipe goes first: without this the older wave of the SIMD wins
+                // the issue port whatever it is doing, and the matrix phases of group 1 run 30 % longer
+                __builtin_amdgcn_s_setprio(3);
                 f32x16 acc;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int i = 0; i < DT; ++i) {   // (the fences keep the issue order as written)
+                for (int i = 0; i < DT; ++i) {
                     score_mfma(i, acc);
                     __builtin_amdgcn_sched_barrier(0);
+                    fetch_k1(i, k_rd);
+                    __builtin_amdgcn_sched_barrier(0);
                     pv_mfma(0, i, pw);
+                    __builtin_amdgcn_sched_barrier(0);
+                    fetch_v1(0, i, v_rd);
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 int in_flight = 0;   // wave-wide requests of this phase still allowed in flight at its end
                 if constexpr (!KV_I8) {
-                    // K tile phi+5 and V tile phi+3 straight into their ring slots; tiles past the last one
-                    // this row block needs are not requested
-                    // (past the end of a pass that continues: tiles 0..3 of the next one)
-                    const int kt = phi + 5, vt = phi + 3, n_req = cont ? n_tiles + kRing : n_tiles;
-                    if (kt < n_req) {
-                        dma_tile(krs_raw, d_koff, kt < n_tiles ? kt : kt - n_tiles, ((P4 + 1) & 3) * TILEB);
+                    // K tile phi+6 and V tile phi+4 straight into their ring slots; tiles past the last one
+                    // this row block needs are not requested, so the ring is quiet when the pass ends
+                    if (phi + 6 < n_tiles) {
+                        dma_tile(krs_raw, d_koff, phi + 6, ((phi + 6) & (kRingK - 1)) * TILEB);
                         in_flight += NLD;
                     }
-                    if (phi > 0 && vt < n_req) {   // (V tile 3 came with the prologue)
-                        dma_tile(vrs_raw, d_voff, vt < n_tiles ? vt : vt - n_tiles, K_BYTES + ((P4 + 3) & 3) * TILEB);
+                    if (phi + 4 < n_tiles) {
+                        dma_tile(vrs_raw, d_voff, phi + 4, K_BYTES + P4 * TILEB);
                         in_flight += NLD;
                     }
                 } else {
-                    // the pieces loaded two phases ago go to K tile phi+3 and V tile phi+1
-                    store_tile(((P4 + 3) & 3) * TILEBK, p_kdst, sg.k);
-                    store_tile(((P4 + 1) & 3) * TILEBV, p_vdst, sg.v);
-                    store_s((P4 + 3) & 3, sg.s);
+                    // the pieces loaded two phases ago go to K tile phi+5 and V tile phi+3
+                    store_tile(((phi + 5) & (kRingK - 1)) * TILEBK, p_kdst, sg.k);
+                    store_tile(((P4 + 3) & 3) * TILEBV, p_vdst, sg.v);
+                    store_s((phi + 5) & (kRingK - 1), sg.s);
                 }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int i = 0; i < DT; ++i) {
                     score_mfma(DT + i, acc);
                     __builtin_amdgcn_sched_barrier(0);
+                    fetch_k1(DT + i, k_rd);
+                    __builtin_amdgcn_sched_barrier(0);
                     pv_mfma(1, i, pw);
+                    __builtin_amdgcn_sched_barrier(0);
+                    fetch_v1(1, i, v_rd);
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 st = acc;
+                __builtin_amdgcn_s_setprio(0);
                 if constexpr (!KV_I8) {
                     // what this wave requested in its previous matrix phase is read from the next phase on
                     if (in_flight == 2 * NLD) __builtin_amdgcn_s_waitcnt(0x0f70 | (2 * NLD));
                     else if (in_flight == NLD) __builtin_amdgcn_s_waitcnt(0x0f70 | NLD);
                     else __builtin_amdgcn_s_waitcnt(0x0f70);
                 } else {
-                    load_tile(krs, phi + 5, sg.k);
-                    load_tile(vrs, phi + 3, sg.v);
-                    load_s(phi + 5, sg.s);
+                    load_tile(krs, phi + 7, sg.k);
+                    load_tile(vrs, phi + 5, sg.v);
+                    load_s(phi + 7, sg.s);
                 }
             }
             // End of phase: this wave's LDS reads and writes are done, then the workgroup barrier.  (Not
@@ -540,25 +532,31 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         };
         auto run = [&](auto grp_c) {
             constexpr int G = decltype(grp_c)::value;
-            // group 0 starts with the scores of tile 0; group 1 computes those of tile 1 in phase 0, which has
-            // no tile -1: nothing but zeros may meet its (zero) probabilities
+            // Group 0 starts with the scores of tile 0 and then reads the operands of its matrix phase 1 (K
+            // tile 2, V tile 0); group 1 reads those of its matrix phase 0 (K tile 1; there is no tile -1,
+            // and nothing but zeros may meet its zero probabilities).
             if (G == 0) {
-                fetch_k(int_c<0>{});
+#pragma unroll
+                for (int s = 0; s < KS; ++s) fetch_k1(s, 0);
 #pragma unroll
                 for (int r = 0; r < 16; ++r) st[r] = 0.0f;
 #pragma unroll
                 for (int s = 0; s < KS; ++s) score_mfma(s, st);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int s = 0; s < KS; ++s) fetch_k1(s, 2 * TILEBK);
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    fetch_v1(0, dt, 0);
+                    fetch_v1(1, dt, 0);
+                }
             } else {
-                fetch_k(int_c<1>{});
+#pragma unroll
+                for (int s = 0; s < KS; ++s) fetch_k1(s, TILEBK);
 #pragma unroll
                 for (int u = 0; u < 2; ++u)
 #pragma unroll
                     for (int i = 0; i < 2 * DT; ++i) vfr[u][i] = s16x4{0, 0, 0, 0};
-            }
-            if constexpr (!KV_I8) {
-                // K tile 4 takes the slot of K tile 0 once every wave of group 0 has read that
-                __syncthreads();
-                if (G == 1 && 4 < n_tiles) dma_tile(krs_raw, d_koff, 4, 0);
             }
             for (int phi = 0; phi <= last_phase; phi += 4) {
                 phase(int_c<0>{}, grp_c, phi);
@@ -572,12 +570,11 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         if (grp == 0) run(int_c<0>{});
         else run(int_c<1>{});
         if (has_next) load_q(x);   // in flight during the merge
-        continued = cont;
 
         // ---- merge the two groups' partial results.  A wave keeps half of its O^T tiles and hands the
         // other half, with its max and row sum, to its partner (same rows, other group) through LDS.
         {
-            f32x4* mg = reinterpret_cast<f32x4*>(smem + RING_BYTES);   // [wave][NV][lane]
+            f32x4* mg = reinterpret_cast<f32x4*>(smem);   // [wave][NV][lane]; the ring is dead and quiet after the last barrier
             const float L = half_sum(lsum);
             constexpr int HALF = DT / 2;
             const int keep0 = grp == 0 ? 0 : HALF;
