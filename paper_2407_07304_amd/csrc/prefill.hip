@@ -558,6 +558,12 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
 #pragma unroll
                     for (int i = 0; i < 2 * DT; ++i) vfr[u][i] = s16x4{0, 0, 0, 0};
             }
+            // these reads are done before phase 0 begins: its matrix phase already sends V tile 4 to the slot
+            // of V tile 0
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
             for (int phi = 0; phi <= last_phase; phi += 4) {
                 phase(int_c<0>{}, grp_c, phi);
                 if (phi + 1 > last_phase) break;
