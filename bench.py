@@ -44,8 +44,11 @@ def measured_traffic():
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--settle-ms", type=float, default=150.0,
+                    help="before the warm-up steps, run untimed steps for this long: the GPU clocks take about 40 ms of "
+                         "load to leave their idle state (the first ~160 steps run up to 1.5x slower)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the INT8 prefill workloads reported beside the headline")
     ap.add_argument("--traffic-probe", action="store_true",
@@ -121,6 +124,11 @@ def main():
             dst.copy_(src)        # reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
         del src, dst
+    t_settle = time.perf_counter()
+    while (time.perf_counter() - t_settle) * 1e3 < args.settle_ms:
+        for _ in range(20):
+            step()
+        torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -179,6 +187,7 @@ def main():
         "workload": "C2 causal prefill B=1 Hq=Hkv=32 S=2048 D=128 bf16 (value); then K,V -> INT8 cache; then "
                     "C4 decode B=16 H=32 D=128 T=8192 INT8 KV (decode.value)",
         "only": args.only, "seeds": {"C2": c2.seed, "C4": c4.seed},
+        "settle_ms": args.settle_ms,   # untimed steps before the warm-up steps, until the clocks have left idle
     }
 
     # ---- INT8-KV prefill workloads beside the headline (device-seeded N(0,1); a few launches each)
