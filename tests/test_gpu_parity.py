@@ -320,3 +320,28 @@ def test_prefill_many_launches_are_bit_identical(sa, oracle, kv_int8):
         differing += int(not torch.equal(out, first))
     torch.cuda.synchronize()
     assert differing == 0
+
+
+def _random_shape(i):
+    rng = np.random.default_rng(1000 + i)
+    hkv = int(rng.integers(1, 4))
+    return dict(B=int(rng.integers(1, 4)), Hkv=hkv, Hq=hkv * int(rng.choice([1, 2, 4])),
+                n=int(rng.choice([rng.integers(1, 40), rng.integers(40, 300), rng.integers(300, 900)])),
+                D=int(rng.choice([64, 128])), causal=bool(rng.integers(0, 2)), kv_int8=bool(rng.integers(0, 2)))
+
+
+@pytest.mark.parametrize("i", range(16))
+def test_prefill_seeded_random_shapes(sa, oracle, i):
+    # lengths that are no multiple of a tile, a row block or a ring depth, batches and head groupings mixed
+    c = _random_shape(i)
+    print("prefill random shape", i, c, flush=True)
+    _prefill_case(sa, oracle, c["B"], c["Hq"], c["Hkv"], c["n"], c["D"], c["causal"], c["kv_int8"], out_f32=bool(i & 1),
+                  seed=2000 + i)
+
+
+@pytest.mark.parametrize("i", range(12))
+def test_decode_seeded_random_shapes(sa, oracle, i):
+    c = _random_shape(100 + i)
+    T = c["n"] * 7 + 1   # up to ~6300 cached tokens: several splits and a ragged last chunk
+    print("decode random shape", i, c, "T", T, flush=True)
+    _decode_case(sa, oracle, c["B"], c["Hq"], c["Hkv"], T, c["D"], seed=3000 + i)
