@@ -92,6 +92,10 @@ size_t slim_attn_decode_int8_workspace_bytes(int batch, int q_heads, int kv_head
  *     s_t = softmax_scale * k_scale[b,g,t] * <q[b,h,:], k_codes[b,g,t,:]>
  *     o[b,h,:] = sum_t softmax_t(s) * v_scale[b,g,t] * v_codes[b,g,t,:]
  * The query is the newest position, so `causal` 0 and 1 give the same result.
+ * With 2 to 32 query heads per KV head (GQA, named beside MHA in section 2.1) the query
+ * heads of a KV head share one pass over its cache: the cache is read once per KV head,
+ * the two products run on the matrix cores, and the probabilities (times v_scale) are
+ * rounded to bf16 before the second product, as in slim_attn_prefill.
  * q_bf16    device, in   [batch, q_heads, 1, head_dim] bf16
  * k_codes, v_codes  device, in  [batch, kv_heads, kv_len, head_dim] int8
  * k_scale, v_scale  device, in  [batch, kv_heads, kv_len] fp32

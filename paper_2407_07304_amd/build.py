@@ -5,11 +5,12 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libslimattn.so")
-SOURCES = ["api.hip", "kv_quant.hip", "decode.hip", "prefill.hip"]
+SOURCES = ["api.hip", "kv_quant.hip", "decode.hip", "decode_gqa.hip", "prefill.hip"]
 # prefill.hip: MFMA results stay in arch VGPRs (no AGPR copies around the softmax), and fmaxf needs no
 # NaN quieting (NaN inputs are documented as undefined).  The quantiser keeps the IEEE defaults.
 # -Wno-inline-asm: its buffer loads with an LDS destination set M0 themselves and say so in the clobber list.
-EXTRA = {"prefill.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form", "-fno-honor-nans", "-mno-amdgpu-ieee", "-Wno-inline-asm"]}
+EXTRA = {"prefill.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form", "-fno-honor-nans", "-mno-amdgpu-ieee", "-Wno-inline-asm"],
+         "decode_gqa.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form", "-fno-honor-nans"]}
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 # Packed-fp32 instructions are switched off for every kernel of this library.

@@ -96,7 +96,7 @@ int slim_attn_prefill(const void* q_bf16, const void* k, const void* v, const fl
 
 size_t slim_attn_decode_int8_workspace_bytes(int batch, int q_heads, int kv_heads, int kv_len, int head_dim) {
     if (check_shape(batch, q_heads, kv_heads, kv_len, head_dim) != SLIM_OK) return 0;
-    return slim::decode_workspace_bytes(batch, q_heads, kv_len, head_dim);
+    return slim::decode_workspace_bytes(batch, q_heads, kv_heads, kv_len, head_dim);
 }
 
 int slim_attn_decode_int8(const void* q_bf16, const int8_t* k_codes, const float* k_scale, const int8_t* v_codes,
@@ -111,7 +111,7 @@ int slim_attn_decode_int8(const void* q_bf16, const int8_t* k_codes, const float
     if (misaligned(q_bf16) || misaligned(k_codes) || misaligned(k_scale) || misaligned(v_codes) ||
         misaligned(v_scale) || misaligned(out_bf16) || misaligned(workspace))
         return SLIM_ERR_ALIGN;
-    if (workspace_bytes < slim::decode_workspace_bytes(batch, q_heads, kv_len, head_dim)) return SLIM_ERR_WORKSPACE;
+    if (workspace_bytes < slim::decode_workspace_bytes(batch, q_heads, kv_heads, kv_len, head_dim)) return SLIM_ERR_WORKSPACE;
     slim::DecodeArgs a;
     a.q = q_bf16;
     a.k_codes = k_codes;

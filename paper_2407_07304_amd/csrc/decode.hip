@@ -259,12 +259,36 @@ int decode_num_splits(int kv_len, long n_bh) {
     return (kv_len + per_block - 1) / per_block;
 }
 
-size_t decode_workspace_bytes(int batch, int q_heads, int kv_len, int head_dim) {
-    const size_t n = (size_t)batch * q_heads * decode_num_splits(kv_len, (long)batch * q_heads);
+bool decode_uses_gqa_kernel(int q_heads, int kv_heads) {
+    const int G = q_heads / kv_heads;
+    return G >= 2 && G <= 32;
+}
+
+size_t decode_workspace_bytes(int batch, int q_heads, int kv_heads, int kv_len, int head_dim) {
+    const int n_split = decode_uses_gqa_kernel(q_heads, kv_heads) ? decode_gqa_num_splits(kv_len, (long)batch * kv_heads)
+                                                                  : decode_num_splits(kv_len, (long)batch * q_heads);
+    const size_t n = (size_t)batch * q_heads * n_split;
     return n * ((size_t)head_dim + 2) * sizeof(float);
 }
 
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t stream) {
+    if (decode_uses_gqa_kernel(a.q_heads, a.kv_heads)) {
+        // the query heads of a KV head share one pass over its cache; every wave's token run is a split
+        const int n_split = decode_gqa_num_splits(a.kv_len, (long)a.batch * a.kv_heads);
+        const size_t n_part = (size_t)a.batch * a.q_heads * n_split;
+        float* ws_acc = a.workspace;
+        float* ws_ml = a.workspace + n_part * a.head_dim;
+        hipError_t e = launch_decode_gqa_split(a, ws_acc, ws_ml, n_split, stream);
+        if (e != hipSuccess) return e;
+        const unsigned nbh = (unsigned)(a.batch * a.q_heads);
+        if (a.head_dim == 128)
+            hipLaunchKernelGGL(slim_decode_combine_kernel<128>, dim3(nbh), dim3(128), 0, stream, ws_acc, ws_ml,
+                               (uint16_t*)a.out, n_split);
+        else
+            hipLaunchKernelGGL(slim_decode_combine_kernel<64>, dim3(nbh), dim3(64), 0, stream, ws_acc, ws_ml,
+                               (uint16_t*)a.out, n_split);
+        return hipGetLastError();
+    }
     const long n_bh = (long)a.batch * a.q_heads;
     const int tpw = decode_tokens_per_wave(a.kv_len, n_bh);
     const int n_split = decode_num_splits(a.kv_len, n_bh);

@@ -58,25 +58,6 @@ struct PrefillParams {
     float scale_log2e;
 };
 
-typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-typedef short s16x8 __attribute__((ext_vector_type(8)));
-
-__device__ __forceinline__ s16x4 lds_read_tr16(const uint16_t* p) {
-    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p));
-}
-
-// value of the other 32-lane half of the wave, combined with op: every lane ends with op(lo, hi)
-__device__ __forceinline__ float half_max(float x) {
-    const unsigned b = __float_as_uint(x);
-    const auto sw = __builtin_amdgcn_permlane32_swap(b, b, false, false);
-    return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-}
-__device__ __forceinline__ float half_sum(float x) {
-    const unsigned b = __float_as_uint(x);
-    const auto sw = __builtin_amdgcn_permlane32_swap(b, b, false, false);
-    return __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
-}
-
 template <int N>
 using int_c = std::integral_constant<int, N>;
 

@@ -37,7 +37,13 @@ struct DecodeArgs {
 // cache of kv_len tokens and n_bh = batch * q_heads independent rows.
 int decode_tokens_per_wave(int kv_len, long n_bh);
 int decode_num_splits(int kv_len, long n_bh);
-size_t decode_workspace_bytes(int batch, int q_heads, int kv_len, int head_dim);
+// Grouped-query variant (2 to 32 query heads per KV head): one wave streams a token run of one (batch, KV
+// head) for all its query heads; every wave is a split.  n_bg = batch * kv_heads.
+bool decode_uses_gqa_kernel(int q_heads, int kv_heads);
+int decode_gqa_tokens_per_wave(int kv_len, long n_bg);
+int decode_gqa_num_splits(int kv_len, long n_bg);
+hipError_t launch_decode_gqa_split(const DecodeArgs& a, float* ws_acc, float* ws_ml, int n_split, hipStream_t stream);
+size_t decode_workspace_bytes(int batch, int q_heads, int kv_heads, int kv_len, int head_dim);
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t stream);
 
 }  // namespace slim

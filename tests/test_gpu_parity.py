@@ -345,3 +345,34 @@ def test_decode_seeded_random_shapes(sa, oracle, i):
     T = c["n"] * 7 + 1   # up to ~6300 cached tokens: several splits and a ragged last chunk
     print("decode random shape", i, c, "T", T, flush=True)
     _decode_case(sa, oracle, c["B"], c["Hq"], c["Hkv"], T, c["D"], seed=3000 + i)
+
+
+@pytest.mark.parametrize("D,Hq,Hkv,T", [(128, 64, 2, 333), (128, 32, 1, 1500), (64, 32, 1, 97), (128, 33, 1, 200),
+                                        (64, 48, 3, 2049), (128, 6, 2, 4100), (128, 16, 1, 31), (128, 24, 8, 129)])
+def test_decode_grouped_query_heads(sa, oracle, D, Hq, Hkv, T):
+    # 2 to 32 query heads per KV head take the kernel that reads the cache once per KV head (one tile, ragged
+    # tails, several tiles per wave, runs that end inside a tile); 33 heads per KV head take the per-head kernel
+    print("decode grouped", D, Hq, Hkv, T, flush=True)
+    _decode_case(sa, oracle, 2, Hq, Hkv, T, D, 70 + T)
+
+
+@pytest.mark.timeout(600)
+def test_decode_llama70b_shape_full_size(sa, oracle):
+    # the grouped-query shape of the paper's larger model: 64 query heads on 8 KV heads, 8192 cached tokens
+    print("decode 64/8 heads, full tensor", flush=True)
+    _decode_case(sa, oracle, 16, 64, 8, 8192, 128, 77)
+
+
+def test_decode_grouped_all_zero_tokens_and_huge_scores(sa, oracle):
+    # tokens whose row is all zero (scale 0) and a softmax scale that makes the scores large
+    rng = np.random.default_rng(78)
+    B, Hq, Hkv, T, D = 1, 8, 2, 700, 128
+    q, k, v = normal_bf16(rng, (B, Hq, 1, D)), normal_bf16(rng, (B, Hkv, T, D)), normal_bf16(rng, (B, Hkv, T, D))
+    k[:, :, 5::7, :] = 0
+    v[:, :, 3::11, :] = 0
+    kc, ks = oracle.kv_quant_int8(k)
+    vc, vs = oracle.kv_quant_int8(v)
+    for scale in (1.0 / math.sqrt(D), 1.0):
+        out = sa.slim_attn_decode_int8(dev_bf16(q), dev(kc), dev(ks), dev(vc), dev(vs), scale)
+        torch.cuda.synchronize()
+        check_close(host_f64(out), oracle.attn(q, kc, vc, scale, False, k_scale=ks, v_scale=vs), "grouped decode, scale %g" % scale)
