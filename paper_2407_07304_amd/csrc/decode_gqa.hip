@@ -82,29 +82,29 @@ __global__ __launch_bounds__(64 * kGqaWaves) void slim_decode_int8_gqa_kernel(
         }
     }
 
-    // Piece lane + 64 n of a tile (row-major, 16 codes each).  Rows past the end of the cache are clamped to the
-    // last row and masked.  Two tiles of loads are in flight per wave (the registers of tile i are refilled with
-    // tile i+2 as soon as they are consumed): with 8 waves per compute unit that is what it takes to cover the
-    // memory latency.
-    const int8_t* const kbase = kc + kvrow0 * D;
-    const int8_t* const vbase = vc + kvrow0 * D;
+    // Piece lane + 64 n of a tile (row-major, 16 codes each), through buffer descriptors that cover exactly this
+    // (batch, KV head)'s slab: rows past the end of the cache read as zero (and are masked) and a load costs one
+    // vector add.  The codes are used once: non-temporal.  Two tiles of
+    // loads are in flight per wave (the registers of tile i are refilled with tile i+2 as soon as they are
+    // consumed): with 8 waves per compute unit that is what it takes to cover the memory latency.
+    const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc((void*)(kc + kvrow0 * D), 0, (int)((unsigned)T * D), 0x00020000);
+    const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc((void*)(vc + kvrow0 * D), 0, (int)((unsigned)T * D), 0x00020000);
     const float* const sbase = (hh == 0 ? ks : vs) + kvrow0;
+    int p_off[NP];
+#pragma unroll
+    for (int n = 0; n < NP; ++n) p_off[n] = ((lane + 64 * n) / CPR) * D + ((lane + 64 * n) % CPR) * 16;
     u32x4 kbuf[2][NP], vbuf[2][NP];
     float sc[2] = {0.0f, 0.0f};
-    auto issue = [&](auto par, const int8_t* base, u32x4 (&buf)[2][NP], int t0) {
+    auto issue = [&](auto par, const __amdgpu_buffer_rsrc_t rs, u32x4 (&buf)[2][NP], int t0) {
         constexpr int P = decltype(par)::value;
 #pragma unroll
-        for (int n = 0; n < NP; ++n) {
-            const int pid = lane + 64 * n;
-            const long row = min(t0 + pid / CPR, T - 1);
-            buf[P][n] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + row * D + (pid % CPR) * 16));
-        }
+        for (int n = 0; n < NP; ++n) buf[P][n] = __builtin_amdgcn_raw_buffer_load_b128(rs, p_off[n] + t0 * D, 0, 2 /* nt */);
     };
     auto issue_k = [&](auto par, int t0) {
-        issue(par, kbase, kbuf, t0);
+        issue(par, krs, kbuf, t0);
         sc[decltype(par)::value] = sbase[min(t0 + l32, T - 1)];
     };
-    auto issue_v = [&](auto par, int t0) { issue(par, vbase, vbuf, t0); };
+    auto issue_v = [&](auto par, int t0) { issue(par, vrs, vbuf, t0); };
     auto stage = [&](auto par, const u32x4 (&buf)[2][NP], char* tile, int pitch) {   // widen a tile into LDS
         constexpr int P = decltype(par)::value;
 #pragma unroll
@@ -171,12 +171,13 @@ __global__ __launch_bounds__(64 * kGqaWaves) void slim_decode_int8_gqa_kernel(
         float u[16];
 #pragma unroll
         for (int r4 = 0; r4 < 4; ++r4) {
-            const f32x4 kf = *reinterpret_cast<const f32x4*>(&scS[8 * r4 + 4 * hh]);
+            const f32x4 kf4 = *reinterpret_cast<const f32x4*>(&scS[8 * r4 + 4 * hh]);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float x = acc[4 * r4 + e] * kf[e];
-                u[4 * r4 + e] = (t0 + 8 * r4 + 4 * hh + e < t_end) ? x : kMasked;
-            }
+            for (int e = 0; e < 4; ++e) u[4 * r4 + e] = acc[4 * r4 + e] * kf4[e];
+        }
+        if (t0 + kGqaTile > t_end) {   // the run ends inside this tile
+#pragma unroll
+            for (int r = 0; r < 16; ++r) u[r] = (t0 + 8 * (r / 4) + 4 * hh + r % 4 < t_end) ? u[r] : kMasked;
         }
         float umax = fmaxf(u[0], u[1]);
 #pragma unroll
@@ -247,15 +248,25 @@ __global__ __launch_bounds__(64 * kGqaWaves) void slim_decode_int8_gqa_kernel(
     }
 }
 
-// One wave streams tokens_per_wave tokens (a multiple of the tile).  Enough waves to fill the chip
-// about 1.5 times over, runs short enough to balance and long enough to amortise a wave's set-up.
+// One wave streams tokens_per_wave tokens (a multiple of the tile), a workgroup four such runs, and k
+// workgroups share one (batch, KV head).  A compute unit holds two workgroups, the chip 512: k is chosen so
+// that (rounds of 512 workgroups) x (tiles per wave + a wave's set-up, about two tiles' worth) is smallest,
+// which avoids a last round that is nearly empty and runs that differ in length.
 int decode_gqa_tokens_per_wave(int kv_len, long n_bg) {
-    const long want_waves = 256L * 8 * 3 / 2;
-    long tpw = ((long)kv_len * n_bg + want_waves - 1) / want_waves;
-    tpw = (tpw + kGqaTile - 1) / kGqaTile * kGqaTile;
-    if (tpw < 4 * kGqaTile) tpw = 4 * kGqaTile;
-    if (tpw > 2048) tpw = 2048;
-    return (int)tpw;
+    const long tiles = ((long)kv_len + kGqaTile - 1) / kGqaTile;
+    long best_k = 1, best_cost = -1;
+    for (long k = 1; k <= 16; ++k) {
+        const long per_wave = (tiles + kGqaWaves * k - 1) / (kGqaWaves * k);
+        const long rounds = (n_bg * k + 511) / 512;
+        const long cost = rounds * (per_wave + 2);
+        if (best_cost < 0 || cost < best_cost) {
+            best_cost = cost;
+            best_k = k;
+        }
+        if (per_wave == 1) break;
+    }
+    const long per_wave = (tiles + kGqaWaves * best_k - 1) / (kGqaWaves * best_k);
+    return (int)(per_wave * kGqaTile);
 }
 
 int decode_gqa_num_splits(int kv_len, long n_bg) {
