@@ -53,7 +53,9 @@ __global__ __launch_bounds__(64 * kGqaWaves) void slim_decode_int8_gqa_kernel(
     // LDS row pitches of the bf16 tiles: the padding spreads the 128-bit K row reads and the V transpose reads over the banks
     constexpr int ROWLK = 2 * D + 16, ROWLV = 2 * D + 64;
     constexpr int TILEK = kGqaTile * ROWLK, TILEV = kGqaTile * ROWLV;
-    constexpr int WAVE_LDS = TILEK + TILEV + 256;   // K tile, V tile, the tile's 32 + 32 scales
+    // one tile buffer per wave: the K tile, and once its fragments are read (LDS runs a wave's accesses in order)
+    // the V tile; then the tile's 32 + 32 scales
+    constexpr int WAVE_LDS = (TILEK > TILEV ? TILEK : TILEV) + 256;
 
     __shared__ __attribute__((aligned(16))) char smem[kGqaWaves * WAVE_LDS];
 
@@ -62,8 +64,8 @@ __global__ __launch_bounds__(64 * kGqaWaves) void slim_decode_int8_gqa_kernel(
     const int G = Hq / Hkv;
     const int sp = blockIdx.x * kGqaWaves + w, g = blockIdx.y, b = blockIdx.z;
     char* const kS = smem + w * WAVE_LDS;
-    char* const vS = kS + TILEK;
-    float* const scS = reinterpret_cast<float*>(vS + TILEV);   // [0,32) k_scale * c, [32,64) v_scale
+    char* const vS = kS;
+    float* const scS = reinterpret_cast<float*>(kS + WAVE_LDS - 256);   // [0,32) k_scale * c, [32,64) v_scale
 
     const long kvrow0 = ((long)b * Hkv + g) * (long)T;
     const int t_begin = sp * tokens_per_wave;
