@@ -110,6 +110,24 @@ int slim_attn_decode_int8(const void* q_bf16, const int8_t* k_codes, const float
                           int batch, int q_heads, int kv_heads, int kv_len, int head_dim,
                           int causal, float softmax_scale, void* stream);
 
+/*
+ * The same decode step for a batch whose sequences have caches of different lengths
+ * (the paper's throughput runs, section 3.2, batch many sequences per step): sequence b
+ * attends to its first kv_lens[b] cached tokens.  The cache tensors keep the layout
+ * [batch, kv_heads, kv_len, head_dim] / [batch, kv_heads, kv_len], kv_len being the
+ * allocated length; what lies past a sequence's own length is never read into the result.
+ * kv_lens   device, in   [batch] int32, 4-byte aligned; a value outside [1, kv_len] is
+ *           taken as the nearest bound (the lengths live on the device, so the library
+ *           cannot reject them without waiting for the stream).
+ * Everything else, including the workspace size (computed from kv_len), as in
+ * slim_attn_decode_int8.
+ */
+int slim_attn_decode_int8_varlen(const void* q_bf16, const int8_t* k_codes, const float* k_scale,
+                                 const int8_t* v_codes, const float* v_scale, const int32_t* kv_lens,
+                                 void* out_bf16, void* workspace, size_t workspace_bytes,
+                                 int batch, int q_heads, int kv_heads, int kv_len, int head_dim,
+                                 int causal, float softmax_scale, void* stream);
+
 /* Name of a status code; pointer to static storage, never NULL. */
 const char* slim_status_string(int status);
 

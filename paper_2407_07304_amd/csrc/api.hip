@@ -99,10 +99,10 @@ size_t slim_attn_decode_int8_workspace_bytes(int batch, int q_heads, int kv_head
     return slim::decode_workspace_bytes(batch, q_heads, kv_heads, kv_len, head_dim);
 }
 
-int slim_attn_decode_int8(const void* q_bf16, const int8_t* k_codes, const float* k_scale, const int8_t* v_codes,
-                          const float* v_scale, void* out_bf16, void* workspace, size_t workspace_bytes, int batch,
-                          int q_heads, int kv_heads, int kv_len, int head_dim, int causal, float softmax_scale,
-                          void* stream) {
+static int decode_common(const void* q_bf16, const int8_t* k_codes, const float* k_scale, const int8_t* v_codes,
+                         const float* v_scale, const int32_t* kv_lens, void* out_bf16, void* workspace,
+                         size_t workspace_bytes, int batch, int q_heads, int kv_heads, int kv_len, int head_dim, int causal,
+                         float softmax_scale, void* stream) {
     if (!q_bf16 || !k_codes || !k_scale || !v_codes || !v_scale || !out_bf16 || !workspace) return SLIM_ERR_NULL;
     const int st = check_shape(batch, q_heads, kv_heads, kv_len, head_dim);
     if (st != SLIM_OK) return st;
@@ -111,6 +111,7 @@ int slim_attn_decode_int8(const void* q_bf16, const int8_t* k_codes, const float
     if (misaligned(q_bf16) || misaligned(k_codes) || misaligned(k_scale) || misaligned(v_codes) ||
         misaligned(v_scale) || misaligned(out_bf16) || misaligned(workspace))
         return SLIM_ERR_ALIGN;
+    if (kv_lens && ((uintptr_t)kv_lens & 3u)) return SLIM_ERR_ALIGN;
     if (workspace_bytes < slim::decode_workspace_bytes(batch, q_heads, kv_heads, kv_len, head_dim)) return SLIM_ERR_WORKSPACE;
     slim::DecodeArgs a;
     a.q = q_bf16;
@@ -120,6 +121,7 @@ int slim_attn_decode_int8(const void* q_bf16, const int8_t* k_codes, const float
     a.v_scale = v_scale;
     a.out = out_bf16;
     a.workspace = (float*)workspace;
+    a.kv_lens = kv_lens;
     a.batch = batch;
     a.q_heads = q_heads;
     a.kv_heads = kv_heads;
@@ -128,6 +130,23 @@ int slim_attn_decode_int8(const void* q_bf16, const int8_t* k_codes, const float
     a.softmax_scale = softmax_scale;
     const hipError_t e = slim::launch_decode(a, (hipStream_t)stream);
     return e == hipSuccess ? SLIM_OK : SLIM_ERR_LAUNCH;
+}
+
+int slim_attn_decode_int8(const void* q_bf16, const int8_t* k_codes, const float* k_scale, const int8_t* v_codes,
+                          const float* v_scale, void* out_bf16, void* workspace, size_t workspace_bytes, int batch,
+                          int q_heads, int kv_heads, int kv_len, int head_dim, int causal, float softmax_scale,
+                          void* stream) {
+    return decode_common(q_bf16, k_codes, k_scale, v_codes, v_scale, nullptr, out_bf16, workspace, workspace_bytes, batch,
+                         q_heads, kv_heads, kv_len, head_dim, causal, softmax_scale, stream);
+}
+
+int slim_attn_decode_int8_varlen(const void* q_bf16, const int8_t* k_codes, const float* k_scale, const int8_t* v_codes,
+                                 const float* v_scale, const int32_t* kv_lens, void* out_bf16, void* workspace,
+                                 size_t workspace_bytes, int batch, int q_heads, int kv_heads, int kv_len, int head_dim,
+                                 int causal, float softmax_scale, void* stream) {
+    if (!kv_lens) return SLIM_ERR_NULL;
+    return decode_common(q_bf16, k_codes, k_scale, v_codes, v_scale, kv_lens, out_bf16, workspace, workspace_bytes, batch,
+                         q_heads, kv_heads, kv_len, head_dim, causal, softmax_scale, stream);
 }
 
 }  // extern "C"

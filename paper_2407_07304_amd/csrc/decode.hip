@@ -51,8 +51,8 @@ template <int D>
 __global__ __launch_bounds__(256) void slim_decode_int8_split_kernel(
     const uint16_t* __restrict__ q, const int8_t* __restrict__ kc, const float* __restrict__ ks,
     const int8_t* __restrict__ vc, const float* __restrict__ vs, uint16_t* __restrict__ out,
-    float* __restrict__ ws_acc, float* __restrict__ ws_ml, int Hq, int Hkv, int T, int n_split, int tokens_per_wave,
-    float scale_log2e) {
+    float* __restrict__ ws_acc, float* __restrict__ ws_ml, const int* __restrict__ kv_lens, int Hq, int Hkv, int T_alloc,
+    int n_split, int tokens_per_wave, float scale_log2e) {
     constexpr int LPR = D / 16;        // lanes per token row
     constexpr int SLOTS = 64 / LPR;    // token rows per load instruction of a wave
     constexpr int CH = LPR;            // rows per slot per chunk: SLOTS * CH == kChunk, one token per lane
@@ -66,7 +66,9 @@ __global__ __launch_bounds__(256) void slim_decode_int8_split_kernel(
     const int c = lane % LPR, s = lane / LPR;
     const int sp = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int g = h / (Hq / Hkv);
-    const long kvbase = ((long)b * Hkv + g) * (long)T;
+    // T_alloc is the cache's allocated length (the row stride); this sequence's first T tokens count
+    const int T = kv_lens ? min(max(kv_lens[b], 1), T_alloc) : T_alloc;
+    const long kvbase = ((long)b * Hkv + g) * (long)T_alloc;
     const int8_t* kp = kc + kvbase * D + c * 16;
     const int8_t* vp = vc + kvbase * D + c * 16;
     const float* ksp = ks + kvbase;
@@ -299,12 +301,12 @@ hipError_t launch_decode(const DecodeArgs& a, hipStream_t stream) {
     dim3 grid((unsigned)n_split, (unsigned)a.q_heads, (unsigned)a.batch);
     if (a.head_dim == 128)
         hipLaunchKernelGGL(slim_decode_int8_split_kernel<128>, grid, dim3(256), 0, stream, (const uint16_t*)a.q,
-                           a.k_codes, a.k_scale, a.v_codes, a.v_scale, (uint16_t*)a.out, ws_acc, ws_ml, a.q_heads,
-                           a.kv_heads, a.kv_len, n_split, tpw, scale_log2e);
+                           a.k_codes, a.k_scale, a.v_codes, a.v_scale, (uint16_t*)a.out, ws_acc, ws_ml, a.kv_lens,
+                           a.q_heads, a.kv_heads, a.kv_len, n_split, tpw, scale_log2e);
     else
         hipLaunchKernelGGL(slim_decode_int8_split_kernel<64>, grid, dim3(256), 0, stream, (const uint16_t*)a.q,
-                           a.k_codes, a.k_scale, a.v_codes, a.v_scale, (uint16_t*)a.out, ws_acc, ws_ml, a.q_heads,
-                           a.kv_heads, a.kv_len, n_split, tpw, scale_log2e);
+                           a.k_codes, a.k_scale, a.v_codes, a.v_scale, (uint16_t*)a.out, ws_acc, ws_ml, a.kv_lens,
+                           a.q_heads, a.kv_heads, a.kv_len, n_split, tpw, scale_log2e);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || n_split == 1) return e;
     const unsigned nbh = (unsigned)(a.batch * a.q_heads);

@@ -45,7 +45,8 @@ template <int D>
 __global__ __launch_bounds__(64 * kGqaWaves) void slim_decode_int8_gqa_kernel(
     const uint16_t* __restrict__ q, const int8_t* __restrict__ kc, const float* __restrict__ ks,
     const int8_t* __restrict__ vc, const float* __restrict__ vs, float* __restrict__ ws_acc,
-    float* __restrict__ ws_ml, int Hq, int Hkv, int T, int n_split, int tokens_per_wave, float scale_log2e) {
+    float* __restrict__ ws_ml, const int* __restrict__ kv_lens, int Hq, int Hkv, int T_alloc, int n_split,
+    int tokens_per_wave, float scale_log2e) {
     constexpr int KS = D / 16;            // k-steps of the score MFMA
     constexpr int DT = D / 32;            // 32-row tiles of O^T
     constexpr int CPR = D / 16;           // 16-byte pieces per row
@@ -67,7 +68,9 @@ __global__ __launch_bounds__(64 * kGqaWaves) void slim_decode_int8_gqa_kernel(
     char* const vS = kS;
     float* const scS = reinterpret_cast<float*>(kS + WAVE_LDS - 256);   // [0,32) k_scale * c, [32,64) v_scale
 
-    const long kvrow0 = ((long)b * Hkv + g) * (long)T;
+    // T_alloc is the cache's allocated length (the row stride); this sequence's first T tokens count
+    const int T = kv_lens ? min(max(kv_lens[b], 1), T_alloc) : T_alloc;
+    const long kvrow0 = ((long)b * Hkv + g) * (long)T_alloc;
     const int t_begin = sp * tokens_per_wave;
     const int t_end = min(T, t_begin + tokens_per_wave);
     const int n_tiles = t_begin < T ? (t_end - t_begin + kGqaTile - 1) / kGqaTile : 0;
@@ -284,12 +287,12 @@ hipError_t launch_decode_gqa_split(const DecodeArgs& a, float* ws_acc, float* ws
     dim3 grid((unsigned)(n_split / kGqaWaves), (unsigned)a.kv_heads, (unsigned)a.batch);
     if (a.head_dim == 128)
         hipLaunchKernelGGL(slim_decode_int8_gqa_kernel<128>, grid, dim3(64 * kGqaWaves), 0, stream,
-                           (const uint16_t*)a.q, a.k_codes, a.k_scale, a.v_codes, a.v_scale, ws_acc, ws_ml, a.q_heads,
-                           a.kv_heads, a.kv_len, n_split, tpw, scale_log2e);
+                           (const uint16_t*)a.q, a.k_codes, a.k_scale, a.v_codes, a.v_scale, ws_acc, ws_ml, a.kv_lens,
+                           a.q_heads, a.kv_heads, a.kv_len, n_split, tpw, scale_log2e);
     else
         hipLaunchKernelGGL(slim_decode_int8_gqa_kernel<64>, grid, dim3(64 * kGqaWaves), 0, stream,
-                           (const uint16_t*)a.q, a.k_codes, a.k_scale, a.v_codes, a.v_scale, ws_acc, ws_ml, a.q_heads,
-                           a.kv_heads, a.kv_len, n_split, tpw, scale_log2e);
+                           (const uint16_t*)a.q, a.k_codes, a.k_scale, a.v_codes, a.v_scale, ws_acc, ws_ml, a.kv_lens,
+                           a.q_heads, a.kv_heads, a.kv_len, n_split, tpw, scale_log2e);
     return hipGetLastError();
 }
 

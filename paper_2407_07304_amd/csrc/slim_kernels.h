@@ -30,6 +30,7 @@ struct DecodeArgs {
     const float* v_scale;
     void* out;
     float* workspace;
+    const int* kv_lens;   // device, [batch]: tokens of each sequence's cache that count (clamped to 1..kv_len), or null: all
     int batch, q_heads, kv_heads, kv_len, head_dim;
     float softmax_scale;
 };

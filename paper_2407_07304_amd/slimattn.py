@@ -41,6 +41,8 @@ def load():
         lib.slim_attn_decode_int8_workspace_bytes.restype = ctypes.c_size_t
         lib.slim_attn_decode_int8.argtypes = [p, p, p, p, p, p, p, ctypes.c_size_t, i, i, i, i, i, i, f, p]
         lib.slim_attn_decode_int8.restype = i
+        lib.slim_attn_decode_int8_varlen.argtypes = [p, p, p, p, p, p, p, p, ctypes.c_size_t, i, i, i, i, i, i, f, p]
+        lib.slim_attn_decode_int8_varlen.restype = i
         lib.slim_status_string.argtypes = [i]
         lib.slim_status_string.restype = ctypes.c_char_p
         _lib = lib
@@ -122,4 +124,28 @@ def slim_attn_decode_int8(q, k_codes, k_scale, v_codes, v_scale, softmax_scale, 
                                         _ptr(v_codes, torch.int8), _ptr(v_scale, torch.float32),
                                         _ptr(out, torch.bfloat16), _ptr(workspace), workspace.numel() * workspace.element_size(),
                                         B, Hq, Hkv, T, D, int(bool(causal)), float(softmax_scale), _stream()))
+    return out
+
+
+def slim_attn_decode_int8_varlen(q, k_codes, k_scale, v_codes, v_scale, kv_lens, softmax_scale, causal=False, out=None,
+                                 workspace=None):
+    """As slim_attn_decode_int8, sequence b attending to its first kv_lens[b] cached tokens (kv_lens [B] int32,
+    on the device)."""
+    B, Hq, one, D = q.shape
+    assert one == 1
+    Hkv, T = k_codes.shape[1], k_codes.shape[2]
+    assert k_codes.shape == (B, Hkv, T, D) and v_codes.shape == k_codes.shape
+    assert k_scale.shape == (B, Hkv, T) and v_scale.shape == (B, Hkv, T)
+    assert kv_lens.shape == (B,)
+    if out is None:
+        out = torch.empty((B, Hq, 1, D), dtype=torch.bfloat16, device=q.device)
+    need = slim_attn_decode_int8_workspace_bytes(B, Hq, Hkv, T, D)
+    if workspace is None:
+        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=q.device)
+    _check(load().slim_attn_decode_int8_varlen(_ptr(q, torch.bfloat16), _ptr(k_codes, torch.int8),
+                                               _ptr(k_scale, torch.float32), _ptr(v_codes, torch.int8),
+                                               _ptr(v_scale, torch.float32), _ptr(kv_lens, torch.int32),
+                                               _ptr(out, torch.bfloat16), _ptr(workspace),
+                                               workspace.numel() * workspace.element_size(), B, Hq, Hkv, T, D,
+                                               int(bool(causal)), float(softmax_scale), _stream()))
     return out

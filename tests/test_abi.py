@@ -26,7 +26,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert {"kv_quant_int8", "slim_attn_prefill", "slim_attn_decode_int8",
+    assert {"kv_quant_int8", "slim_attn_prefill", "slim_attn_decode_int8", "slim_attn_decode_int8_varlen",
             "slim_attn_decode_int8_workspace_bytes", "slim_status_string"} <= set(names)
     for n in names:
         assert getattr(lib, n) is not None
@@ -93,3 +93,15 @@ def test_decode_rejects_bad_arguments_and_reports_workspace(lib):
     assert call(D=32) == 3
     assert call(out=A + 2) == 4
     assert call(wsb=ws(1, 2, 2, 100, 128) - 1) == 5
+
+
+def test_varlen_decode_rejects_bad_arguments(lib):
+    f = lib.slim_attn_decode_int8_varlen
+
+    def call(lens=A, q=A, wsp=A, wsb=1 << 30, T=100, D=128):
+        return f(P(q), P(A), P(A), P(A), P(A), P(lens), P(A), P(wsp), wsb, 1, 2, 2, T, D, 0, 0.1, None)
+
+    assert call(lens=None) == 1 and call(q=None) == 1
+    assert call(lens=A + 2) == 4 and call(q=A + 4) == 4
+    assert call(T=0) == 2 and call(D=96) == 3
+    assert call(wsb=8) == 5

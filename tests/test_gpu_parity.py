@@ -376,3 +376,39 @@ def test_decode_grouped_all_zero_tokens_and_huge_scores(sa, oracle):
         out = sa.slim_attn_decode_int8(dev_bf16(q), dev(kc), dev(ks), dev(vc), dev(vs), scale)
         torch.cuda.synchronize()
         check_close(host_f64(out), oracle.attn(q, kc, vc, scale, False, k_scale=ks, v_scale=vs), "grouped decode, scale %g" % scale)
+
+
+@pytest.mark.parametrize("D,Hq,Hkv", [(128, 4, 4), (128, 16, 2), (64, 8, 8), (64, 6, 3)])
+def test_decode_per_sequence_lengths(sa, oracle, D, Hq, Hkv):
+    # every sequence attends to its own number of cached tokens (one tile, ragged tails, the whole allocation);
+    # what lies past a sequence's length in the cache must not reach the result: it is filled with huge codes
+    rng = np.random.default_rng(81 + D + Hq)
+    B, T = 6, 1500
+    lens = np.array([1, 31, 32, 700, 1499, 1500], dtype=np.int32)
+    q = normal_bf16(rng, (B, Hq, 1, D))
+    k, v = normal_bf16(rng, (B, Hkv, T, D)), normal_bf16(rng, (B, Hkv, T, D))
+    kc, ks = oracle.kv_quant_int8(k)
+    vc, vs = oracle.kv_quant_int8(v)
+    kc2, ks2, vc2, vs2 = kc.copy(), ks.copy(), vc.copy(), vs.copy()
+    for b in range(B):
+        kc2[b, :, lens[b]:] = 127
+        vc2[b, :, lens[b]:] = -127
+        ks2[b, :, lens[b]:] = 1.0e6
+        vs2[b, :, lens[b]:] = 1.0e6
+    scale = 1.0 / math.sqrt(D)
+    out = sa.slim_attn_decode_int8_varlen(dev_bf16(q), dev(kc2), dev(ks2), dev(vc2), dev(vs2),
+                                          torch.from_numpy(lens).cuda(), scale)
+    torch.cuda.synchronize()
+    # (the tolerance is that of an output tensor: max-abs over everything, mean-abs over the batch.  A sequence of
+    # one token returns v_0 times its v_scale rounded to bf16 in the grouped-query kernel, a relative error of up
+    # to 2^-9 on every element of that row, so a single short row sits near the mean-abs limit by itself.)
+    def expect(lengths):
+        return np.concatenate([oracle.attn(q[b:b + 1], kc[b:b + 1, :, :n], vc[b:b + 1, :, :n], scale, False,
+                                           k_scale=ks[b:b + 1, :, :n], v_scale=vs[b:b + 1, :, :n])
+                               for b, n in enumerate(lengths)], axis=0)
+    check_close(host_f64(out), expect([int(n) for n in lens]), "decode with per-sequence lengths")
+    # lengths outside [1, T] are taken as the nearest bound
+    lens2 = np.array([0, -5, 1, 1501, 99999, 1500], dtype=np.int32)
+    out2 = sa.slim_attn_decode_int8_varlen(dev_bf16(q), dev(kc), dev(ks), dev(vc), dev(vs), torch.from_numpy(lens2).cuda(), scale)
+    torch.cuda.synchronize()
+    check_close(host_f64(out2), expect([1, 1, 1, 1500, 1500, 1500]), "decode with clamped lengths")
