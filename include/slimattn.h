@@ -59,6 +59,23 @@ int kv_quant_int8(const void* x_bf16, int8_t* codes, float* scales,
                   int causal, float softmax_scale, void* stream);
 
 /*
+ * Appends one token per sequence to an INT8 cache: the step before a decode over it
+ * (section 2.2 keeps the cache in INT8, so every new token's K and V are quantised on
+ * their way in).  Row (b, g) of x_new is quantised exactly as in kv_quant_int8 and
+ * written at token index positions[b] of that (batch, KV head)'s cache.
+ * x_new_bf16  device, in      [batch, kv_heads, 1, head_dim] bf16
+ * codes       device, in/out  [batch, kv_heads, kv_len, head_dim] int8 (kv_len = allocated length)
+ * scales      device, in/out  [batch, kv_heads, kv_len] fp32
+ * positions   device, in      [batch] int32, 4-byte aligned; a sequence whose position lies
+ *             outside [0, kv_len) is skipped (the positions live on the device, so the
+ *             library cannot reject them without waiting for the stream).
+ * q_heads, causal and softmax_scale belong to the common argument tail and are ignored.
+ */
+int kv_quant_int8_append(const void* x_new_bf16, int8_t* codes, float* scales, const int32_t* positions,
+                         int batch, int q_heads, int kv_heads, int kv_len, int head_dim,
+                         int causal, float softmax_scale, void* stream);
+
+/*
  * Prefill attention (section 2.1).  For every batch b, query head h and query row i:
  *     s_j = softmax_scale * <q[b,h,i,:], k^[b,g,j,:]>   over the visible keys j
  *     o[b,h,i,:] = sum_j softmax_j(s) * v^[b,g,j,:]

@@ -60,6 +60,22 @@ int kv_quant_int8(const void* x_bf16, int8_t* codes, float* scales, int batch, i
     return e == hipSuccess ? SLIM_OK : SLIM_ERR_LAUNCH;
 }
 
+int kv_quant_int8_append(const void* x_new_bf16, int8_t* codes, float* scales, const int32_t* positions, int batch,
+                         int q_heads, int kv_heads, int kv_len, int head_dim, int causal, float softmax_scale,
+                         void* stream) {
+    (void)q_heads;
+    (void)causal;
+    (void)softmax_scale;
+    if (!x_new_bf16 || !codes || !scales || !positions) return SLIM_ERR_NULL;
+    const int st = check_shape(batch, kv_heads, kv_heads, kv_len, head_dim);
+    if (st != SLIM_OK) return st;
+    if (misaligned(x_new_bf16) || misaligned(codes) || misaligned(scales)) return SLIM_ERR_ALIGN;
+    if ((uintptr_t)positions & 3u) return SLIM_ERR_ALIGN;
+    const hipError_t e = slim::launch_kv_quant_int8_append(x_new_bf16, codes, scales, positions, batch, kv_heads, kv_len,
+                                                           head_dim, (hipStream_t)stream);
+    return e == hipSuccess ? SLIM_OK : SLIM_ERR_LAUNCH;
+}
+
 int slim_attn_prefill(const void* q_bf16, const void* k, const void* v, const float* k_scale, const float* v_scale,
                       void* out, int batch, int q_heads, int kv_heads, int seq_len, int head_dim, int causal,
                       float softmax_scale, int kv_dtype, int out_dtype, void* stream) {

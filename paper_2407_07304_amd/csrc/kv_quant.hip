@@ -10,6 +10,34 @@
 
 namespace slim {
 
+// One row: this lane's 8 values (of the LPR lanes that hold the row) -> its 8 codes and the row's scale.
+template <int LPR>
+__device__ __forceinline__ void quant_row_piece(const u32x4 raw, u32x2& out2, float& scale) {
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        v[2 * i] = bf16_bits_to_f32(raw[i] & 0xffffu);
+        v[2 * i + 1] = __uint_as_float(raw[i] & 0xffff0000u);
+    }
+    float amax = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(v[i]));
+#pragma unroll
+    for (int off = 1; off < LPR; off <<= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
+    scale = amax / 127.0f;   // IEEE division, one rounding
+    unsigned int packed[2] = {0u, 0u};
+    if (amax != 0.0f) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            float r = rintf(v[i] / scale);   // IEEE division, then ties-to-even
+            r = fminf(fmaxf(r, -127.0f), 127.0f);
+            packed[i / 4] |= ((unsigned int)(int)r & 0xffu) << (8 * (i % 4));
+        }
+    }
+    out2[0] = packed[0];
+    out2[1] = packed[1];
+}
+
 template <int D>
 __global__ __launch_bounds__(256) void kv_quant_int8_kernel(const uint16_t* __restrict__ x, int8_t* __restrict__ codes,
                                                             float* __restrict__ scales, long n_rows) {
@@ -20,33 +48,34 @@ __global__ __launch_bounds__(256) void kv_quant_int8_kernel(const uint16_t* __re
     const long stride = (long)gridDim.x * ROWS;
     for (long row = row0; row < n_rows; row += stride) {   // rows past the end leave whole row groups idle together
         const u32x4 raw = *reinterpret_cast<const u32x4*>(x + row * D + lane_in_row * 8);
-        float v[8];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            v[2 * i] = bf16_bits_to_f32(raw[i] & 0xffffu);
-            v[2 * i + 1] = __uint_as_float(raw[i] & 0xffff0000u);
-        }
-        float amax = 0.0f;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(v[i]));
-#pragma unroll
-        for (int off = 1; off < LPR; off <<= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
-        const float scale = amax / 127.0f;   // IEEE division, one rounding
-        unsigned int packed[2] = {0u, 0u};
-        if (amax != 0.0f) {
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                float r = rintf(v[i] / scale);   // IEEE division, then ties-to-even
-                r = fminf(fmaxf(r, -127.0f), 127.0f);
-                packed[i / 4] |= ((unsigned int)(int)r & 0xffu) << (8 * (i % 4));
-            }
-        }
         u32x2 out2;
-        out2[0] = packed[0];
-        out2[1] = packed[1];
+        float scale;
+        quant_row_piece<LPR>(raw, out2, scale);
         *reinterpret_cast<u32x2*>(codes + row * D + lane_in_row * 8) = out2;
         if (lane_in_row == 0) scales[row] = scale;
     }
+}
+
+// One new token per (batch, KV head): row r = b * Hkv + g of x goes to token positions[b] of that head's cache.
+template <int D>
+__global__ __launch_bounds__(256) void kv_quant_int8_append_kernel(const uint16_t* __restrict__ x, int8_t* __restrict__ codes,
+                                                                   float* __restrict__ scales,
+                                                                   const int* __restrict__ positions, int n_rows, int Hkv,
+                                                                   int T) {
+    constexpr int LPR = D / 8;
+    constexpr int ROWS = 256 / LPR;
+    const int lane_in_row = threadIdx.x % LPR;
+    const int row = blockIdx.x * ROWS + threadIdx.x / LPR;
+    if (row >= n_rows) return;   // (whole row groups leave together: the shuffles below stay inside a row)
+    const u32x4 raw = *reinterpret_cast<const u32x4*>(x + (long)row * D + lane_in_row * 8);
+    u32x2 out2;
+    float scale;
+    quant_row_piece<LPR>(raw, out2, scale);
+    const int pos = positions[row / Hkv];
+    if (pos < 0 || pos >= T) return;   // no room in this sequence's cache: nothing is written
+    const long out_row = (long)row * T + pos;
+    *reinterpret_cast<u32x2*>(codes + out_row * D + lane_in_row * 8) = out2;
+    if (lane_in_row == 0) scales[out_row] = scale;
 }
 
 hipError_t launch_kv_quant_int8(const void* x, int8_t* codes, float* scales, long n_rows, int head_dim,
@@ -61,6 +90,20 @@ hipError_t launch_kv_quant_int8(const void* x, int8_t* codes, float* scales, lon
     else
         hipLaunchKernelGGL(kv_quant_int8_kernel<64>, dim3((unsigned)blocks), dim3(256), 0, stream,
                            (const uint16_t*)x, codes, scales, n_rows);
+    return hipGetLastError();
+}
+
+hipError_t launch_kv_quant_int8_append(const void* x, int8_t* codes, float* scales, const int* positions, int batch,
+                                       int kv_heads, int kv_len, int head_dim, hipStream_t stream) {
+    const int n_rows = batch * kv_heads;
+    const int rows_per_block = 256 / (head_dim / 8);
+    const unsigned blocks = (unsigned)((n_rows + rows_per_block - 1) / rows_per_block);
+    if (head_dim == 128)
+        hipLaunchKernelGGL(kv_quant_int8_append_kernel<128>, dim3(blocks), dim3(256), 0, stream, (const uint16_t*)x, codes,
+                           scales, positions, n_rows, kv_heads, kv_len);
+    else
+        hipLaunchKernelGGL(kv_quant_int8_append_kernel<64>, dim3(blocks), dim3(256), 0, stream, (const uint16_t*)x, codes,
+                           scales, positions, n_rows, kv_heads, kv_len);
     return hipGetLastError();
 }
 

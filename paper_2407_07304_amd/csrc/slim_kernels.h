@@ -9,6 +9,9 @@ namespace slim {
 hipError_t launch_kv_quant_int8(const void* x, int8_t* codes, float* scales, long n_rows, int head_dim,
                                 hipStream_t stream);
 
+hipError_t launch_kv_quant_int8_append(const void* x, int8_t* codes, float* scales, const int* positions, int batch,
+                                       int kv_heads, int kv_len, int head_dim, hipStream_t stream);
+
 struct PrefillArgs {
     const void* q;
     const void* k;

@@ -35,6 +35,8 @@ def load():
         p, i, f = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
         lib.kv_quant_int8.argtypes = [p, p, p, i, i, i, i, i, i, f, p]
         lib.kv_quant_int8.restype = i
+        lib.kv_quant_int8_append.argtypes = [p, p, p, p, i, i, i, i, i, i, f, p]
+        lib.kv_quant_int8_append.restype = i
         lib.slim_attn_prefill.argtypes = [p, p, p, p, p, p, i, i, i, i, i, i, f, i, i, p]
         lib.slim_attn_prefill.restype = i
         lib.slim_attn_decode_int8_workspace_bytes.argtypes = [i, i, i, i, i]
@@ -149,3 +151,14 @@ def slim_attn_decode_int8_varlen(q, k_codes, k_scale, v_codes, v_scale, kv_lens,
                                                workspace.numel() * workspace.element_size(), B, Hq, Hkv, T, D,
                                                int(bool(causal)), float(softmax_scale), _stream()))
     return out
+
+
+def kv_quant_int8_append(x_new, codes, scales, positions):
+    """Quantises x_new [B,Hkv,1,D] bf16 into token positions[b] of the cache (codes [B,Hkv,T,D] int8, scales
+    [B,Hkv,T] fp32, both updated in place); positions [B] int32 on the device."""
+    B, Hkv, one, D = x_new.shape
+    assert one == 1
+    T = codes.shape[2]
+    assert codes.shape == (B, Hkv, T, D) and scales.shape == (B, Hkv, T) and positions.shape == (B,)
+    _check(load().kv_quant_int8_append(_ptr(x_new, torch.bfloat16), _ptr(codes, torch.int8), _ptr(scales, torch.float32),
+                                       _ptr(positions, torch.int32), B, Hkv, Hkv, T, D, 0, 1.0, _stream()))

@@ -27,7 +27,7 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert {"kv_quant_int8", "slim_attn_prefill", "slim_attn_decode_int8", "slim_attn_decode_int8_varlen",
-            "slim_attn_decode_int8_workspace_bytes", "slim_status_string"} <= set(names)
+            "kv_quant_int8_append", "slim_attn_decode_int8_workspace_bytes", "slim_status_string"} <= set(names)
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -105,3 +105,15 @@ def test_varlen_decode_rejects_bad_arguments(lib):
     assert call(lens=A + 2) == 4 and call(q=A + 4) == 4
     assert call(T=0) == 2 and call(D=96) == 3
     assert call(wsb=8) == 5
+
+
+def test_append_rejects_bad_arguments(lib):
+    f = lib.kv_quant_int8_append
+
+    def call(x=A, codes=A, scales=A, pos=A, B=2, Hkv=2, T=100, D=128):
+        return f(P(x), P(codes), P(scales), P(pos), B, 1, Hkv, T, D, 0, 1.0, None)
+
+    assert call(x=None) == 1 and call(pos=None) == 1 and call(scales=None) == 1
+    assert call(T=0) == 2 and call(B=0) == 2
+    assert call(D=100) == 3
+    assert call(codes=A + 8) == 4 and call(pos=A + 1) == 4

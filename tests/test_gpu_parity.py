@@ -412,3 +412,47 @@ def test_decode_per_sequence_lengths(sa, oracle, D, Hq, Hkv):
     out2 = sa.slim_attn_decode_int8_varlen(dev_bf16(q), dev(kc), dev(ks), dev(vc), dev(vs), torch.from_numpy(lens2).cuda(), scale)
     torch.cuda.synchronize()
     check_close(host_f64(out2), expect([1, 1, 1, 1500, 1500, 1500]), "decode with clamped lengths")
+
+
+@pytest.mark.parametrize("D,Hq,Hkv", [(128, 8, 2), (64, 4, 4)])
+def test_append_then_decode_serving_step(sa, oracle, D, Hq, Hkv):
+    # one step of a serving loop: the new token's K and V rows are quantised into each sequence's cache at its
+    # own position, then every sequence attends to its cache including the new token
+    rng = np.random.default_rng(90 + D)
+    B, T = 5, 600
+    lens = np.array([0, 1, 31, 300, 599], dtype=np.int32)          # tokens cached so far = position of the new one
+    pos = np.array([0, 1, 31, 300, 599], dtype=np.int32)
+    q = normal_bf16(rng, (B, Hq, 1, D))
+    k, v = normal_bf16(rng, (B, Hkv, T, D)), normal_bf16(rng, (B, Hkv, T, D))
+    k_new, v_new = normal_bf16(rng, (B, Hkv, 1, D)), normal_bf16(rng, (B, Hkv, 1, D))
+    k_new[2, 0] = 0                                                  # an all-zero row: scale 0, codes 0
+    kc, ks = oracle.kv_quant_int8(k)
+    vc, vs = oracle.kv_quant_int8(v)
+    dkc, dks, dvc, dvs = dev(kc), dev(ks), dev(vc), dev(vs)
+    dpos = torch.from_numpy(pos).cuda()
+    sa.kv_quant_int8_append(dev_bf16(k_new), dkc, dks, dpos)
+    sa.kv_quant_int8_append(dev_bf16(v_new), dvc, dvs, dpos)
+    torch.cuda.synchronize()
+    # the cache afterwards: the oracle's codes and scale of the new row at its position, nothing else touched
+    knc, kns = oracle.kv_quant_int8(k_new)
+    vnc, vns = oracle.kv_quant_int8(v_new)
+    for b in range(B):
+        kc[b, :, pos[b]] = knc[b, :, 0]
+        ks[b, :, pos[b]] = kns[b, :, 0]
+        vc[b, :, pos[b]] = vnc[b, :, 0]
+        vs[b, :, pos[b]] = vns[b, :, 0]
+    assert np.array_equal(dkc.cpu().numpy(), kc) and np.array_equal(dvc.cpu().numpy(), vc)
+    assert np.array_equal(dks.cpu().numpy().view(np.uint32), ks.view(np.uint32))
+    assert np.array_equal(dvs.cpu().numpy().view(np.uint32), vs.view(np.uint32))
+    # a position outside the cache writes nothing
+    bad = torch.from_numpy(np.array([-1, T, T + 5, -7, 1 << 30], dtype=np.int32)).cuda()
+    sa.kv_quant_int8_append(dev_bf16(k_new), dkc, dks, bad)
+    torch.cuda.synchronize()
+    assert np.array_equal(dkc.cpu().numpy(), kc)
+    scale = 1.0 / math.sqrt(D)
+    out = sa.slim_attn_decode_int8_varlen(dev_bf16(q), dkc, dks, dvc, dvs, torch.from_numpy(lens + 1).cuda(), scale)
+    torch.cuda.synchronize()
+    want = np.concatenate([oracle.attn(q[b:b + 1], kc[b:b + 1, :, :n + 1], vc[b:b + 1, :, :n + 1], scale, False,
+                                       k_scale=ks[b:b + 1, :, :n + 1], v_scale=vs[b:b + 1, :, :n + 1])
+                           for b, n in enumerate(lens)], axis=0)
+    check_close(host_f64(out), want, "append + decode")
