@@ -456,3 +456,29 @@ def test_append_then_decode_serving_step(sa, oracle, D, Hq, Hkv):
                                        k_scale=ks[b:b + 1, :, :n + 1], v_scale=vs[b:b + 1, :, :n + 1])
                            for b, n in enumerate(lens)], axis=0)
     check_close(host_f64(out), want, "append + decode")
+
+
+def test_calls_follow_the_current_stream(sa, oracle):
+    # every entry point enqueues on the stream it is given: a chain of calls on a side stream, with no
+    # synchronisation in between, gives bit for bit what the default stream gives
+    rng = np.random.default_rng(95)
+    B, Hq, Hkv, S, D = 1, 8, 2, 520, 128
+    q, k, v = (dev_bf16(normal_bf16(rng, shp)) for shp in ((B, Hq, S, D), (B, Hkv, S, D), (B, Hkv, S, D)))
+    scale = 1.0 / math.sqrt(D)
+
+    def chain():
+        kc, ks = sa.kv_quant_int8(k)
+        vc, vs = sa.kv_quant_int8(v)
+        pre = sa.slim_attn_prefill(q, kc, vc, scale, True, k_scale=ks, v_scale=vs)
+        dec = sa.slim_attn_decode_int8(q[:, :, S - 1:S].contiguous(), kc, ks, vc, vs, scale)
+        return kc, ks, pre, dec
+
+    ref = chain()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        got = chain()
+    side.synchronize()
+    for a, b in zip(ref, got):
+        assert torch.equal(a, b)
