@@ -222,21 +222,26 @@ __global__ __launch_bounds__(256) void slim_decode_int8_split_kernel(
 }
 
 // Merges the n_split partial (max, sum, accumulator) triples of one (batch, head) in
-// split order and writes the bf16 output row.
+// split order and writes the bf16 output row.  The loops are unrolled by eight so that eight
+// splits' loads are in flight at a time: with many splits (short batches of long caches)
+// a loop that waits for every load costs more than the split kernel itself.
 template <int D>
 __global__ __launch_bounds__(D) void slim_decode_combine_kernel(const float* __restrict__ ws_acc,
                                                                 const float* __restrict__ ws_ml,
                                                                 uint16_t* __restrict__ out, int n_split) {
     const long bh = blockIdx.x;
     const int d = threadIdx.x;
+    const float* const ml = ws_ml + bh * n_split * 2;
+    const float* const acc = ws_acc + bh * n_split * D + d;
     float M = kMasked;
-    for (int sp = 0; sp < n_split; ++sp) M = fmaxf(M, ws_ml[(bh * n_split + sp) * 2]);
+#pragma unroll 8
+    for (int sp = 0; sp < n_split; ++sp) M = fmaxf(M, ml[2 * sp]);
     float L = 0.0f, o = 0.0f;
+#pragma unroll 8
     for (int sp = 0; sp < n_split; ++sp) {
-        const long idx = bh * n_split + sp;
-        const float f = fast_exp2(ws_ml[idx * 2] - M);
-        L = fmaf(f, ws_ml[idx * 2 + 1], L);
-        o = fmaf(f, ws_acc[idx * D + d], o);
+        const float f = fast_exp2(ml[2 * sp] - M);
+        L = fmaf(f, ml[2 * sp + 1], L);
+        o = fmaf(f, acc[(long)sp * D], o);
     }
     out[bh * D + d] = (uint16_t)(pack_bf16x2(o / L, 0.0f) & 0xffffu);
 }
