@@ -482,3 +482,43 @@ def test_calls_follow_the_current_stream(sa, oracle):
     side.synchronize()
     for a, b in zip(ref, got):
         assert torch.equal(a, b)
+
+
+def test_closed_forms_on_the_gpu(sa, oracle):
+    # checks that need no oracle: equal keys give the running mean of V (causal) or its mean (decode); one key that
+    # dominates every score returns its V row.  bf16 K/V for prefill, the INT8 cache for decode (both kernels).
+    rng = np.random.default_rng(97)
+    B, H, S, D = 1, 4, 300, 128
+    q = normal_bf16(rng, (B, H, S, D))
+    v = normal_bf16(rng, (B, H, S, D))
+    k_same = np.broadcast_to(normal_bf16(rng, (B, H, 1, D)), (B, H, S, D)).copy()
+    scale = 1.0 / math.sqrt(D)
+    vf = (v.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    run_mean = np.cumsum(vf, axis=2) / np.arange(1, S + 1)[None, None, :, None]
+    out = sa.slim_attn_prefill(dev_bf16(q), dev_bf16(k_same), dev_bf16(v), scale, True, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    check_close(host_f64(out), run_mean, "equal keys: running mean of V")
+    for Hq, Hkv in ((4, 4), (8, 2)):
+        qd = normal_bf16(rng, (B, Hq, 1, D))
+        kd = np.broadcast_to(normal_bf16(rng, (B, Hkv, 1, D)), (B, Hkv, S, D)).copy()
+        vd = normal_bf16(rng, (B, Hkv, S, D))
+        kc, ks = oracle.kv_quant_int8(kd)
+        vc, vs = oracle.kv_quant_int8(vd)
+        dec = sa.slim_attn_decode_int8(dev_bf16(qd), dev(kc), dev(ks), dev(vc), dev(vs), scale)
+        torch.cuda.synchronize()
+        v_hat = vc.astype(np.float64) * vs.astype(np.float64)[..., None]
+        mean_v = np.repeat(v_hat.mean(axis=2, keepdims=True), Hq // Hkv, axis=1)
+        check_close(host_f64(dec), mean_v, "equal keys: mean of the dequantised V (decode %d/%d)" % (Hq, Hkv))
+    # one dominant key: key j0 is 8 q_i / |q_i| for no i in particular, so use a key aligned with every query: all
+    # queries equal; the key at j0 equals the query scaled up, the others are orthogonal noise scaled down
+    q1 = np.broadcast_to(normal_bf16(rng, (B, H, 1, D)), (B, H, S, D)).copy()
+    q1f = (q1.astype(np.uint32) << 16).view(np.float32)
+    k_small = (0.01 * rng.standard_normal((B, H, S, D))).astype(np.float32)
+    j0 = 3
+    k_small[:, :, j0] = 4.0 * q1f[:, :, 0]
+    from paper_2407_07304_amd.inputs import f32_to_bf16_bits
+    kb = f32_to_bf16_bits(k_small)
+    out = sa.slim_attn_prefill(dev_bf16(q1), dev_bf16(kb), dev_bf16(v), 1.0, False, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    want = np.broadcast_to(vf[:, :, j0:j0 + 1], (B, H, S, D))
+    check_close(host_f64(out), want, "one dominant key returns its V row")
