@@ -244,6 +244,21 @@ def main():
                 del ob, diff
             extras.append(rec)
             del qx, kx, vx, kcx, vcx, ksx, vsx, ox
+        # ---- C2 prefill that also writes the INT8 cache, against the step's own prefill + two quantiser launches
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(50)]
+        for i in range(60):
+            step()
+            if i >= 10:
+                evs[i - 10][0].record()
+            sa.slim_attn_prefill_emit_int8(q2, k2, v2, c2.softmax_scale, True, out=o2)
+            if i >= 10:
+                evs[i - 10][1].record()
+        torch.cuda.synchronize()
+        te = np.array([a.elapsed_time(b) for a, b in evs])
+        extras.append({"workload": "C2 causal prefill that also emits the INT8 K/V cache (one launch)",
+                       "ms": round(float(te.mean()), 4), "ms_median": round(float(np.median(te)), 4),
+                       "separate_launches_ms": round(float(pre_ms + quant_ms), 4)})
+
         # ---- decode on the grouped-query shape of the paper's larger model (64 query heads on 8 KV heads)
         Bg, Hqg, Hkvg, Tg, Dg = 16, 64, 8, 8192, 128
         g = torch.Generator(device="cuda")

@@ -97,6 +97,21 @@ int slim_attn_prefill(const void* q_bf16, const void* k, const void* v,
                       int causal, float softmax_scale, int kv_dtype, int out_dtype, void* stream);
 
 /*
+ * Prefill attention on bf16 K/V that also writes their INT8 cache in the same launch (the
+ * serving loop of section 2.2 keeps K/V in INT8 from the first token on): the attention
+ * result is that of slim_attn_prefill with kv_dtype == SLIM_BF16, bit for bit, and
+ * codes/scales are those of kv_quant_int8 on k_bf16 and v_bf16, bit for bit.  Each row
+ * block's own K and V rows are quantised by the workgroup that just attended over them.
+ * k_codes, v_codes  device, out  [batch, kv_heads, seq_len, head_dim] int8
+ * k_scale, v_scale  device, out  [batch, kv_heads, seq_len] fp32
+ * Everything else as in slim_attn_prefill.
+ */
+int slim_attn_prefill_emit_int8(const void* q_bf16, const void* k_bf16, const void* v_bf16, void* out,
+                                int8_t* k_codes, float* k_scale, int8_t* v_codes, float* v_scale,
+                                int batch, int q_heads, int kv_heads, int seq_len, int head_dim,
+                                int causal, float softmax_scale, int out_dtype, void* stream);
+
+/*
  * Bytes of device workspace slim_attn_decode_int8 needs for this shape (partial
  * max / sum / accumulator of each split of the key axis).  0 if the shape is invalid.
  */

@@ -76,9 +76,10 @@ int kv_quant_int8_append(const void* x_new_bf16, int8_t* codes, float* scales, c
     return e == hipSuccess ? SLIM_OK : SLIM_ERR_LAUNCH;
 }
 
-int slim_attn_prefill(const void* q_bf16, const void* k, const void* v, const float* k_scale, const float* v_scale,
-                      void* out, int batch, int q_heads, int kv_heads, int seq_len, int head_dim, int causal,
-                      float softmax_scale, int kv_dtype, int out_dtype, void* stream) {
+static int prefill_common(const void* q_bf16, const void* k, const void* v, const float* k_scale, const float* v_scale,
+                          void* out, int8_t* k_codes_out, float* k_scale_out, int8_t* v_codes_out, float* v_scale_out,
+                          int batch, int q_heads, int kv_heads, int seq_len, int head_dim, int causal,
+                          float softmax_scale, int kv_dtype, int out_dtype, void* stream) {
     if (!q_bf16 || !k || !v || !out) return SLIM_ERR_NULL;
     if (kv_dtype != SLIM_BF16 && kv_dtype != SLIM_I8) return SLIM_ERR_UNSUPPORTED;
     if (out_dtype != SLIM_BF16 && out_dtype != SLIM_F32) return SLIM_ERR_UNSUPPORTED;
@@ -90,6 +91,8 @@ int slim_attn_prefill(const void* q_bf16, const void* k, const void* v, const fl
     if (!(softmax_scale > 0.0f) || !isfinite(softmax_scale)) return SLIM_ERR_SHAPE;
     if (misaligned(q_bf16) || misaligned(k) || misaligned(v) || misaligned(out)) return SLIM_ERR_ALIGN;
     if (kv_dtype == SLIM_I8 && (misaligned(k_scale) || misaligned(v_scale))) return SLIM_ERR_ALIGN;
+    if (k_codes_out && (misaligned(k_codes_out) || misaligned(k_scale_out) || misaligned(v_codes_out) || misaligned(v_scale_out)))
+        return SLIM_ERR_ALIGN;
     slim::PrefillArgs a;
     a.q = q_bf16;
     a.k = k;
@@ -97,6 +100,10 @@ int slim_attn_prefill(const void* q_bf16, const void* k, const void* v, const fl
     a.k_scale = k_scale;
     a.v_scale = v_scale;
     a.out = out;
+    a.k_codes_out = k_codes_out;
+    a.k_scale_out = k_scale_out;
+    a.v_codes_out = v_codes_out;
+    a.v_scale_out = v_scale_out;
     a.batch = batch;
     a.q_heads = q_heads;
     a.kv_heads = kv_heads;
@@ -108,6 +115,21 @@ int slim_attn_prefill(const void* q_bf16, const void* k, const void* v, const fl
     a.out_f32 = out_dtype == SLIM_F32;
     const hipError_t e = slim::launch_prefill(a, (hipStream_t)stream);
     return e == hipSuccess ? SLIM_OK : SLIM_ERR_LAUNCH;
+}
+
+int slim_attn_prefill(const void* q_bf16, const void* k, const void* v, const float* k_scale, const float* v_scale,
+                      void* out, int batch, int q_heads, int kv_heads, int seq_len, int head_dim, int causal,
+                      float softmax_scale, int kv_dtype, int out_dtype, void* stream) {
+    return prefill_common(q_bf16, k, v, k_scale, v_scale, out, nullptr, nullptr, nullptr, nullptr, batch, q_heads, kv_heads,
+                          seq_len, head_dim, causal, softmax_scale, kv_dtype, out_dtype, stream);
+}
+
+int slim_attn_prefill_emit_int8(const void* q_bf16, const void* k_bf16, const void* v_bf16, void* out, int8_t* k_codes,
+                                float* k_scale, int8_t* v_codes, float* v_scale, int batch, int q_heads, int kv_heads,
+                                int seq_len, int head_dim, int causal, float softmax_scale, int out_dtype, void* stream) {
+    if (!k_codes || !k_scale || !v_codes || !v_scale) return SLIM_ERR_NULL;
+    return prefill_common(q_bf16, k_bf16, v_bf16, nullptr, nullptr, out, k_codes, k_scale, v_codes, v_scale, batch, q_heads,
+                          kv_heads, seq_len, head_dim, causal, softmax_scale, SLIM_BF16, out_dtype, stream);
 }
 
 size_t slim_attn_decode_int8_workspace_bytes(int batch, int q_heads, int kv_heads, int kv_len, int head_dim) {

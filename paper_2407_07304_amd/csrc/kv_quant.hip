@@ -10,34 +10,6 @@
 
 namespace slim {
 
-// One row: this lane's 8 values (of the LPR lanes that hold the row) -> its 8 codes and the row's scale.
-template <int LPR>
-__device__ __forceinline__ void quant_row_piece(const u32x4 raw, u32x2& out2, float& scale) {
-    float v[8];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        v[2 * i] = bf16_bits_to_f32(raw[i] & 0xffffu);
-        v[2 * i + 1] = __uint_as_float(raw[i] & 0xffff0000u);
-    }
-    float amax = 0.0f;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) amax = fmaxf(amax, fabsf(v[i]));
-#pragma unroll
-    for (int off = 1; off < LPR; off <<= 1) amax = fmaxf(amax, __shfl_xor(amax, off));
-    scale = amax / 127.0f;   // IEEE division, one rounding
-    unsigned int packed[2] = {0u, 0u};
-    if (amax != 0.0f) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            float r = rintf(v[i] / scale);   // IEEE division, then ties-to-even
-            r = fminf(fmaxf(r, -127.0f), 127.0f);
-            packed[i / 4] |= ((unsigned int)(int)r & 0xffu) << (8 * (i % 4));
-        }
-    }
-    out2[0] = packed[0];
-    out2[1] = packed[1];
-}
-
 template <int D>
 __global__ __launch_bounds__(256) void kv_quant_int8_kernel(const uint16_t* __restrict__ x, int8_t* __restrict__ codes,
                                                             float* __restrict__ scales, long n_rows) {

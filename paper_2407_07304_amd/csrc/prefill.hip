@@ -54,6 +54,10 @@ struct PrefillParams {
     const float* ks;
     const float* vs;
     void* out;
+    int8_t* kq;    // INT8 cache to write next to the attention (bf16 K/V only), or null
+    float* kqs;
+    int8_t* vq;
+    float* vqs;
     int Hq, Hkv, S, causal, n_rb, n_pair, total, chunk;
     float scale_log2e;
 };
@@ -612,6 +616,35 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
                     }
                 }
         }
+
+        // ---- the INT8 cache of this row block's own K and V rows, if asked for (section 2.2): the workgroup of
+        // a KV head's first query head quantises them, 16 rows per wave, with the quantiser's row routine.
+        // The rows were this row block's last tiles, so they come from the L2.
+        if constexpr (!KV_I8) {
+            if (p.kq != nullptr && h % (p.Hq / p.Hkv) == 0) {
+                constexpr int LPR = D / 8;          // lanes per row
+                constexpr int RPI = 64 / LPR;       // rows per wave-wide access
+#pragma unroll
+                for (int ten = 0; ten < 2; ++ten) {
+                    const uint16_t* src = (const uint16_t*)(ten == 0 ? p.k : p.v) + kvrow0 * D;
+                    int8_t* codes = (ten == 0 ? p.kq : p.vq) + kvrow0 * D;
+                    float* scales = (ten == 0 ? p.kqs : p.vqs) + kvrow0;
+#pragma unroll
+                    for (int j = 0; j < 16 / RPI; ++j) {
+                        const int row = i0 + 16 * w8 + RPI * j + l / LPR;
+                        const int piece = l % LPR;
+                        const u32x4 raw = *reinterpret_cast<const u32x4*>(src + (long)min(row, S - 1) * D + piece * 8);
+                        u32x2 cw;
+                        float scale;
+                        quant_row_piece<LPR>(raw, cw, scale);
+                        if (row < S) {
+                            *reinterpret_cast<u32x2*>(codes + (long)row * D + piece * 8) = cw;
+                            if (piece == 0) scales[row] = scale;
+                        }
+                    }
+                }
+            }
+        }
     }
 }
 
@@ -631,6 +664,10 @@ hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream) {
     p.ks = a.k_scale;
     p.vs = a.v_scale;
     p.out = a.out;
+    p.kq = a.k_codes_out;
+    p.kqs = a.k_scale_out;
+    p.vq = a.v_codes_out;
+    p.vqs = a.v_scale_out;
     p.Hq = a.q_heads;
     p.Hkv = a.kv_heads;
     p.S = a.seq_len;

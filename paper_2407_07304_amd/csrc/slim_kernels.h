@@ -19,6 +19,10 @@ struct PrefillArgs {
     const float* k_scale;
     const float* v_scale;
     void* out;
+    int8_t* k_codes_out;   // with bf16 K/V: also write their INT8 cache (all four set), or all null
+    float* k_scale_out;
+    int8_t* v_codes_out;
+    float* v_scale_out;
     int batch, q_heads, kv_heads, seq_len, head_dim, causal;
     float softmax_scale;
     bool kv_int8, out_f32;

@@ -39,6 +39,8 @@ def load():
         lib.kv_quant_int8_append.restype = i
         lib.slim_attn_prefill.argtypes = [p, p, p, p, p, p, i, i, i, i, i, i, f, i, i, p]
         lib.slim_attn_prefill.restype = i
+        lib.slim_attn_prefill_emit_int8.argtypes = [p, p, p, p, p, p, p, p, i, i, i, i, i, i, f, i, p]
+        lib.slim_attn_prefill_emit_int8.restype = i
         lib.slim_attn_decode_int8_workspace_bytes.argtypes = [i, i, i, i, i]
         lib.slim_attn_decode_int8_workspace_bytes.restype = ctypes.c_size_t
         lib.slim_attn_decode_int8.argtypes = [p, p, p, p, p, p, p, ctypes.c_size_t, i, i, i, i, i, i, f, p]
@@ -162,3 +164,22 @@ def kv_quant_int8_append(x_new, codes, scales, positions):
     assert codes.shape == (B, Hkv, T, D) and scales.shape == (B, Hkv, T) and positions.shape == (B,)
     _check(load().kv_quant_int8_append(_ptr(x_new, torch.bfloat16), _ptr(codes, torch.int8), _ptr(scales, torch.float32),
                                        _ptr(positions, torch.int32), B, Hkv, Hkv, T, D, 0, 1.0, _stream()))
+
+
+def slim_attn_prefill_emit_int8(q, k, v, softmax_scale, causal=True, out=None, out_dtype=torch.bfloat16):
+    """Prefill on bf16 K/V that also writes their INT8 cache: returns (out, k_codes, k_scale, v_codes, v_scale)."""
+    B, Hq, S, D = q.shape
+    Hkv = k.shape[1]
+    assert k.shape == (B, Hkv, S, D) and v.shape == k.shape and k.dtype == torch.bfloat16 and v.dtype == torch.bfloat16
+    if out is None:
+        out = torch.empty((B, Hq, S, D), dtype=out_dtype, device=q.device)
+    kc = torch.empty((B, Hkv, S, D), dtype=torch.int8, device=q.device)
+    vc = torch.empty_like(kc)
+    ks = torch.empty((B, Hkv, S), dtype=torch.float32, device=q.device)
+    vs = torch.empty_like(ks)
+    _check(load().slim_attn_prefill_emit_int8(_ptr(q, torch.bfloat16), _ptr(k, torch.bfloat16), _ptr(v, torch.bfloat16),
+                                              _ptr(out), _ptr(kc, torch.int8), _ptr(ks, torch.float32),
+                                              _ptr(vc, torch.int8), _ptr(vs, torch.float32), B, Hq, Hkv, S, D,
+                                              int(bool(causal)), float(softmax_scale),
+                                              SLIM_F32 if out.dtype == torch.float32 else SLIM_BF16, _stream()))
+    return out, kc, ks, vc, vs

@@ -27,7 +27,7 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert {"kv_quant_int8", "slim_attn_prefill", "slim_attn_decode_int8", "slim_attn_decode_int8_varlen",
-            "kv_quant_int8_append", "slim_attn_decode_int8_workspace_bytes", "slim_status_string"} <= set(names)
+            "kv_quant_int8_append", "slim_attn_prefill_emit_int8", "slim_attn_decode_int8_workspace_bytes", "slim_status_string"} <= set(names)
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -117,3 +117,15 @@ def test_append_rejects_bad_arguments(lib):
     assert call(T=0) == 2 and call(B=0) == 2
     assert call(D=100) == 3
     assert call(codes=A + 8) == 4 and call(pos=A + 1) == 4
+
+
+def test_prefill_emit_rejects_bad_arguments(lib):
+    f = lib.slim_attn_prefill_emit_int8
+
+    def call(q=A, k=A, v=A, out=A, kc=A, ks=A, vc=A, vs=A, S=100, D=128, od=0):
+        return f(P(q), P(k), P(v), P(out), P(kc), P(ks), P(vc), P(vs), 1, 4, 2, S, D, 1, 0.1, od, None)
+
+    assert call(kc=None) == 1 and call(vs=None) == 1 and call(q=None) == 1
+    assert call(S=0) == 2
+    assert call(D=96) == 3 and call(od=7) == 3
+    assert call(vc=A + 4) == 4 and call(k=A + 2) == 4

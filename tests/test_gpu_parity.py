@@ -522,3 +522,29 @@ def test_closed_forms_on_the_gpu(sa, oracle):
     torch.cuda.synchronize()
     want = np.broadcast_to(vf[:, :, j0:j0 + 1], (B, H, S, D))
     check_close(host_f64(out), want, "one dominant key returns its V row")
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,S,D,causal", [(1, 4, 4, 300, 128, True), (2, 8, 2, 517, 128, True), (1, 4, 2, 130, 64, False),
+                                                (1, 2, 2, 1, 128, True), (1, 6, 3, 1000, 64, True)])
+def test_prefill_that_emits_the_int8_cache(sa, oracle, B, Hq, Hkv, S, D, causal):
+    # one launch: the attention of the plain bf16 prefill, bit for bit, and the oracle quantiser's codes and scales
+    rng = np.random.default_rng(99 + S)
+    q, k, v = normal_bf16(rng, (B, Hq, S, D)), normal_bf16(rng, (B, Hkv, S, D)), normal_bf16(rng, (B, Hkv, S, D))
+    if S > 40:   # rows the quantiser treats specially: all zero, one non-zero, subnormal and huge values
+        k[0, 0, 7] = 0
+        v[0, 0, 9] = 0
+        v[0, 0, 9, 5] = 0x3f80
+        k[0, 0, 11] = 0x0001
+        v[0, 0, 12] = 0x7f7f
+    scale = 1.0 / math.sqrt(D)
+    dq, dk, dv = dev_bf16(q), dev_bf16(k), dev_bf16(v)
+    ref = sa.slim_attn_prefill(dq, dk, dv, scale, causal)
+    out, kc, ks, vc, vs = sa.slim_attn_prefill_emit_int8(dq, dk, dv, scale, causal)
+    torch.cuda.synchronize()
+    fin = torch.isfinite(ref.float())
+    assert torch.equal(out[fin], ref[fin]) and torch.equal(torch.isfinite(out.float()), fin)
+    okc, oks = oracle.kv_quant_int8(k)
+    ovc, ovs = oracle.kv_quant_int8(v)
+    assert np.array_equal(kc.cpu().numpy(), okc) and np.array_equal(vc.cpu().numpy(), ovc)
+    assert np.array_equal(ks.cpu().numpy().view(np.uint32), oks.view(np.uint32))
+    assert np.array_equal(vs.cpu().numpy().view(np.uint32), ovs.view(np.uint32))
