@@ -624,19 +624,28 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
             if (p.kq != nullptr && h % (p.Hq / p.Hkv) == 0) {
                 constexpr int LPR = D / 8;          // lanes per row
                 constexpr int RPI = 64 / LPR;       // rows per wave-wide access
+                constexpr int NJ = 16 / RPI;        // accesses per wave and tensor
+                u32x4 raw[2][NJ];
+#pragma unroll
+                for (int ten = 0; ten < 2; ++ten) {   // all the loads first: their latencies overlap
+                    const uint16_t* src = (const uint16_t*)(ten == 0 ? p.k : p.v) + kvrow0 * D;
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) {
+                        const int row = i0 + 16 * w8 + RPI * j + l / LPR;
+                        raw[ten][j] = *reinterpret_cast<const u32x4*>(src + (long)min(row, S - 1) * D + (l % LPR) * 8);
+                    }
+                }
 #pragma unroll
                 for (int ten = 0; ten < 2; ++ten) {
-                    const uint16_t* src = (const uint16_t*)(ten == 0 ? p.k : p.v) + kvrow0 * D;
                     int8_t* codes = (ten == 0 ? p.kq : p.vq) + kvrow0 * D;
                     float* scales = (ten == 0 ? p.kqs : p.vqs) + kvrow0;
 #pragma unroll
-                    for (int j = 0; j < 16 / RPI; ++j) {
+                    for (int j = 0; j < NJ; ++j) {
                         const int row = i0 + 16 * w8 + RPI * j + l / LPR;
                         const int piece = l % LPR;
-                        const u32x4 raw = *reinterpret_cast<const u32x4*>(src + (long)min(row, S - 1) * D + piece * 8);
                         u32x2 cw;
                         float scale;
-                        quant_row_piece<LPR>(raw, cw, scale);
+                        quant_row_piece<LPR>(raw[ten][j], cw, scale);
                         if (row < S) {
                             *reinterpret_cast<u32x2*>(codes + (long)row * D + piece * 8) = cw;
                             if (piece == 0) scales[row] = scale;
