@@ -259,6 +259,24 @@ def main():
                        "ms": round(float(te.mean()), 4), "ms_median": round(float(np.median(te)), 4),
                        "separate_launches_ms": round(float(pre_ms + quant_ms), 4)})
 
+        # ---- C2 in the two-sweep order (row maxima first, then the exponentials against them), beside the
+        # one-sweep kernel the step times
+        ws2 = torch.empty((c2.batch * c2.q_heads * c2.seq_len * 2,), dtype=torch.float32, device="cuda")
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(50)]
+        for i in range(60):
+            step()
+            if i >= 10:
+                evs[i - 10][0].record()
+            sa.slim_attn_prefill_two_sweep(q2, k2, v2, c2.softmax_scale, True, out=o2, workspace=ws2)
+            if i >= 10:
+                evs[i - 10][1].record()
+        torch.cuda.synchronize()
+        tt = np.array([a.elapsed_time(b) for a, b in evs])
+        extras.append({"workload": "C2 causal prefill in two sweeps over K (comparison variant, two launches)",
+                       "ms": round(float(tt.mean()), 4), "ms_median": round(float(np.median(tt)), 4),
+                       "one_sweep_ms": round(float(pre_ms), 4)})
+        del ws2
+
         # ---- decode on the grouped-query shape of the paper's larger model (64 query heads on 8 KV heads)
         Bg, Hqg, Hkvg, Tg, Dg = 16, 64, 8, 8192, 128
         g = torch.Generator(device="cuda")

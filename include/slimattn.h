@@ -38,7 +38,7 @@ enum {
     SLIM_ERR_SHAPE = 2,       /* a size is <= 0, too large to index, q_heads % kv_heads != 0, bad scale/flag */
     SLIM_ERR_UNSUPPORTED = 3, /* head_dim not in {64, 128}, or an unknown dtype code */
     SLIM_ERR_ALIGN = 4,       /* a pointer is not 16-byte aligned */
-    SLIM_ERR_WORKSPACE = 5,   /* workspace smaller than slim_attn_decode_int8_workspace_bytes() */
+    SLIM_ERR_WORKSPACE = 5,   /* workspace smaller than the entry point's *_workspace_bytes() */
     SLIM_ERR_LAUNCH = 6       /* the HIP runtime refused a kernel launch */
 };
 
@@ -108,6 +108,24 @@ int slim_attn_prefill(const void* q_bf16, const void* k, const void* v,
  */
 int slim_attn_prefill_emit_int8(const void* q_bf16, const void* k_bf16, const void* v_bf16, void* out,
                                 int8_t* k_codes, float* k_scale, int8_t* v_codes, float* v_scale,
+                                int batch, int q_heads, int kv_heads, int seq_len, int head_dim,
+                                int causal, float softmax_scale, int out_dtype, void* stream);
+
+/*
+ * Comparison variant of the bf16 prefill that follows the order of operations of section 2.1
+ * literally: a row block's whole score row exists before its softmax is applied.  The scores
+ * of a row block do not fit on chip, so K is swept twice, in two kernel launches: the first
+ * computes the scores and keeps the row maxima (in the workspace), the second computes them
+ * again, exponentiates against those final maxima and multiplies by V.  Same result as
+ * slim_attn_prefill up to rounding order; 1.5 times its matrix work.  It is there to be
+ * measured against the one-sweep kernel, not to be served from.
+ * workspace  device, scratch, at least slim_attn_prefill_two_sweep_workspace_bytes(...) bytes
+ *            (two fp32 per query row); contents before and after the call are meaningless.
+ * K/V are bf16; everything else as in slim_attn_prefill.
+ */
+size_t slim_attn_prefill_two_sweep_workspace_bytes(int batch, int q_heads, int kv_heads, int seq_len, int head_dim);
+int slim_attn_prefill_two_sweep(const void* q_bf16, const void* k_bf16, const void* v_bf16, void* out,
+                                void* workspace, size_t workspace_bytes,
                                 int batch, int q_heads, int kv_heads, int seq_len, int head_dim,
                                 int causal, float softmax_scale, int out_dtype, void* stream);
 

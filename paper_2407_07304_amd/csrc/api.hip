@@ -79,7 +79,7 @@ int kv_quant_int8_append(const void* x_new_bf16, int8_t* codes, float* scales, c
 static int prefill_common(const void* q_bf16, const void* k, const void* v, const float* k_scale, const float* v_scale,
                           void* out, int8_t* k_codes_out, float* k_scale_out, int8_t* v_codes_out, float* v_scale_out,
                           int batch, int q_heads, int kv_heads, int seq_len, int head_dim, int causal,
-                          float softmax_scale, int kv_dtype, int out_dtype, void* stream) {
+                          float softmax_scale, int kv_dtype, int out_dtype, float* row_max, void* stream) {
     if (!q_bf16 || !k || !v || !out) return SLIM_ERR_NULL;
     if (kv_dtype != SLIM_BF16 && kv_dtype != SLIM_I8) return SLIM_ERR_UNSUPPORTED;
     if (out_dtype != SLIM_BF16 && out_dtype != SLIM_F32) return SLIM_ERR_UNSUPPORTED;
@@ -113,6 +113,7 @@ static int prefill_common(const void* q_bf16, const void* k, const void* v, cons
     a.softmax_scale = softmax_scale;
     a.kv_int8 = kv_dtype == SLIM_I8;
     a.out_f32 = out_dtype == SLIM_F32;
+    a.row_max = row_max;
     const hipError_t e = slim::launch_prefill(a, (hipStream_t)stream);
     return e == hipSuccess ? SLIM_OK : SLIM_ERR_LAUNCH;
 }
@@ -121,7 +122,23 @@ int slim_attn_prefill(const void* q_bf16, const void* k, const void* v, const fl
                       void* out, int batch, int q_heads, int kv_heads, int seq_len, int head_dim, int causal,
                       float softmax_scale, int kv_dtype, int out_dtype, void* stream) {
     return prefill_common(q_bf16, k, v, k_scale, v_scale, out, nullptr, nullptr, nullptr, nullptr, batch, q_heads, kv_heads,
-                          seq_len, head_dim, causal, softmax_scale, kv_dtype, out_dtype, stream);
+                          seq_len, head_dim, causal, softmax_scale, kv_dtype, out_dtype, nullptr, stream);
+}
+
+size_t slim_attn_prefill_two_sweep_workspace_bytes(int batch, int q_heads, int kv_heads, int seq_len, int head_dim) {
+    if (check_shape(batch, q_heads, kv_heads, seq_len, head_dim) != SLIM_OK) return 0;
+    return (size_t)batch * q_heads * seq_len * 2 * sizeof(float);
+}
+
+int slim_attn_prefill_two_sweep(const void* q_bf16, const void* k_bf16, const void* v_bf16, void* out, void* workspace,
+                                size_t workspace_bytes, int batch, int q_heads, int kv_heads, int seq_len, int head_dim,
+                                int causal, float softmax_scale, int out_dtype, void* stream) {
+    if (!workspace) return SLIM_ERR_NULL;
+    if (misaligned(workspace)) return SLIM_ERR_ALIGN;
+    const size_t need = slim_attn_prefill_two_sweep_workspace_bytes(batch, q_heads, kv_heads, seq_len, head_dim);
+    if (need != 0 && workspace_bytes < need) return SLIM_ERR_WORKSPACE;
+    return prefill_common(q_bf16, k_bf16, v_bf16, nullptr, nullptr, out, nullptr, nullptr, nullptr, nullptr, batch, q_heads,
+                          kv_heads, seq_len, head_dim, causal, softmax_scale, SLIM_BF16, out_dtype, (float*)workspace, stream);
 }
 
 int slim_attn_prefill_emit_int8(const void* q_bf16, const void* k_bf16, const void* v_bf16, void* out, int8_t* k_codes,
@@ -129,7 +146,7 @@ int slim_attn_prefill_emit_int8(const void* q_bf16, const void* k_bf16, const vo
                                 int seq_len, int head_dim, int causal, float softmax_scale, int out_dtype, void* stream) {
     if (!k_codes || !k_scale || !v_codes || !v_scale) return SLIM_ERR_NULL;
     return prefill_common(q_bf16, k_bf16, v_bf16, nullptr, nullptr, out, k_codes, k_scale, v_codes, v_scale, batch, q_heads,
-                          kv_heads, seq_len, head_dim, causal, softmax_scale, SLIM_BF16, out_dtype, stream);
+                          kv_heads, seq_len, head_dim, causal, softmax_scale, SLIM_BF16, out_dtype, nullptr, stream);
 }
 
 size_t slim_attn_decode_int8_workspace_bytes(int batch, int q_heads, int kv_heads, int kv_len, int head_dim) {

@@ -54,6 +54,7 @@ struct PrefillParams {
     const float* ks;
     const float* vs;
     void* out;
+    float* row_max;   // the two-sweep variant's row maxima [batch, q_heads, seq_len, 2], else null
     int8_t* kq;    // INT8 cache to write next to the attention (bf16 K/V only), or null
     float* kqs;
     int8_t* vq;
@@ -65,8 +66,16 @@ struct PrefillParams {
 template <int N>
 using int_c = std::integral_constant<int, N>;
 
-template <int D, bool KV_I8, bool OUT_F32>
+// MODE 1 and 2: the paper's own order of operations (section 2.1: the whole score row is there before the softmax
+// is applied), for comparison.  A row block's scores do not fit on chip, so K is swept twice, by two launches
+// of this kernel: MODE 1 computes the scores and keeps only the row maxima (one per row and wave group, written
+// to p.row_max), MODE 2 computes them again, exponentiates against those final maxima and multiplies by V:
+// no running maximum, no rescaling of the accumulator, 1.5 times the MFMAs.  MODE 0 is the kernel proper.
+template <int D, bool KV_I8, bool OUT_F32, int MODE = 0>
 __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const PrefillParams p) {
+    static_assert(!(MODE != 0 && KV_I8), "the two-sweep variant exists for bf16 K/V only");
+    constexpr bool TWO_SWEEP = MODE != 0;
+    constexpr bool stats_only = MODE == 1;
     constexpr int KS = D / 16;       // k-steps of the score MFMA
     constexpr int DT = D / 32;       // 32-row tiles of O^T
     constexpr int ROWB = KV_I8 ? D : 2 * D;   // bytes per K/V row in memory
@@ -252,10 +261,6 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         const int lim = p.causal ? min(my_q, S - 1) : S - 1;   // last key this lane's row may see
 
         if (pass == 0) load_q(rb);   // (the second pass's Q is requested before the first one's merge)
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o[dt][r] = 0.0f;
         float M = kMasked, lsum = 0.0f;   // running max in scaled (log2) units; per-lane partial row sum
 
         // ---- prologue.  In the steady state a group stages in its matrix phase phi: bf16 requests K tile
@@ -264,21 +269,32 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         // earlier is staged here, all requests issued together.  Every V slot gets a tile (zeros past the
         // end of the sequence): whatever a skipped tile later leaves in place is finite data of this row
         // block, never the previous pass's merge buffer.
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[dt][r] = 0.0f;
+        if constexpr (MODE == 2) {   // the final maximum of this lane's row over this group's tiles
+            M = p.row_max[((((long)b * p.Hq + h) * S + min(my_q, S - 1)) * 2) + grp];
+        }
         Stage sg;
-        __syncthreads();   // the previous pass has finished with the merge buffer, which lies over the ring
+        __syncthreads();   // the previous pass (or sweep) has finished with the ring and the merge buffer that lies over it
         if constexpr (!KV_I8) {
             if (grp == 0) {
                 dma_tile(krs_raw, d_koff, 0, 0);
                 dma_tile(krs_raw, d_koff, 2, 2 * TILEB);
                 dma_tile(krs_raw, d_koff, 4, 4 * TILEB);
-                dma_tile(vrs_raw, d_voff, 0, K_BYTES);
-                dma_tile(vrs_raw, d_voff, 2, K_BYTES + 2 * TILEB);
+                if (!stats_only) {
+                    dma_tile(vrs_raw, d_voff, 0, K_BYTES);
+                    dma_tile(vrs_raw, d_voff, 2, K_BYTES + 2 * TILEB);
+                }
             } else {
                 dma_tile(krs_raw, d_koff, 1, TILEB);
                 dma_tile(krs_raw, d_koff, 3, 3 * TILEB);
                 dma_tile(krs_raw, d_koff, 5, 5 * TILEB);
-                dma_tile(vrs_raw, d_voff, 1, K_BYTES + TILEB);
-                dma_tile(vrs_raw, d_voff, 3, K_BYTES + 3 * TILEB);
+                if (!stats_only) {
+                    dma_tile(vrs_raw, d_voff, 1, K_BYTES + TILEB);
+                    dma_tile(vrs_raw, d_voff, 3, K_BYTES + 3 * TILEB);
+                }
             }
             __builtin_amdgcn_s_waitcnt(0x0f70);   // vmcnt(0): this wave's requests have landed in LDS
         } else {
@@ -423,6 +439,15 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
                 for (int i = 0; i < 4; ++i) pw[u][i] = pack_bf16x2(a[8 * u + 2 * i], a[8 * u + 2 * i + 1]);
         };
 
+        // MODE 1: the tile's scores only raise the row maximum
+        auto row_max_only = [&](int t, const f32x16& st) {
+            if (t > t_last) return;
+            const int rel = t == t_last ? lim - (t * kBC + 4 * hh) : kBC;   // keys of this lane up to offset rel are visible
+            float umax = kMasked;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) umax = fmaxf(umax, (8 * (r / 4) + (r % 4) <= rel) ? st[r] * c : kMasked);
+            M = fmaxf(M, half_max(umax));
+        };
         f32x16 st;
 #pragma unroll
         for (int r = 0; r < 16; ++r) st[r] = 0.0f;
@@ -434,7 +459,13 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         auto phase = [&](auto p4_c, auto grp_c, int phi) {
             constexpr int P4 = decltype(p4_c)::value, G = decltype(grp_c)::value;
             if constexpr ((P4 & 1) == G) {
-                softmax(phi & (kRingK - 1), phi, st, pw);
+                if constexpr (MODE == 1) {
+                    row_max_only(phi, st);
+                } else {
+                    // (MODE 2: the running maximum starts at the final one, so the overflow watch never
+                    // fires and the masked tile's rescale is by one)
+                    softmax(phi & (kRingK - 1), phi, st, pw);
+                }
             } else {
                 // Matrix phase of tile t = phi - 1: its P V MFMAs and the score MFMAs of tile t + 2, always all
                 // sixteen (a skipped tile has P = 0, unused scores are dropped), alternating so that the score
@@ -457,9 +488,11 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
                     __builtin_amdgcn_sched_barrier(0);
                     fetch_k1(i, k_rd);
                     __builtin_amdgcn_sched_barrier(0);
-                    pv_mfma(0, i, pw);
-                    __builtin_amdgcn_sched_barrier(0);
-                    fetch_v1(0, i, v_rd);
+                    if (!stats_only) {
+                        pv_mfma(0, i, pw);
+                        __builtin_amdgcn_sched_barrier(0);
+                        fetch_v1(0, i, v_rd);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 int in_flight = 0;   // wave-wide requests of this phase still allowed in flight at its end
@@ -470,7 +503,7 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
                         dma_tile(krs_raw, d_koff, phi + 6, ((phi + 6) & (kRingK - 1)) * TILEB);
                         in_flight += NLD;
                     }
-                    if (phi + 4 < n_tiles) {
+                    if (phi + 4 < n_tiles && !stats_only) {
                         dma_tile(vrs_raw, d_voff, phi + 4, K_BYTES + P4 * TILEB);
                         in_flight += NLD;
                     }
@@ -487,9 +520,11 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
                     __builtin_amdgcn_sched_barrier(0);
                     fetch_k1(DT + i, k_rd);
                     __builtin_amdgcn_sched_barrier(0);
-                    pv_mfma(1, i, pw);
-                    __builtin_amdgcn_sched_barrier(0);
-                    fetch_v1(1, i, v_rd);
+                    if (!stats_only) {
+                        pv_mfma(1, i, pw);
+                        __builtin_amdgcn_sched_barrier(0);
+                        fetch_v1(1, i, v_rd);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                 }
                 st = acc;
@@ -530,10 +565,12 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int s = 0; s < KS; ++s) fetch_k1(s, 2 * TILEBK);
+                if (!stats_only) {
 #pragma unroll
-                for (int dt = 0; dt < DT; ++dt) {
-                    fetch_v1(0, dt, 0);
-                    fetch_v1(1, dt, 0);
+                    for (int dt = 0; dt < DT; ++dt) {
+                        fetch_v1(0, dt, 0);
+                        fetch_v1(1, dt, 0);
+                    }
                 }
             } else {
 #pragma unroll
@@ -560,6 +597,11 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         };
         if (grp == 0) run(int_c<0>{});
         else run(int_c<1>{});
+        if constexpr (MODE == 1) {   // this sweep's result: the row maxima; nothing to merge, nothing to store
+            if (hh == 0 && my_q < S) p.row_max[((((long)b * p.Hq + h) * S + my_q) * 2) + grp] = M;
+            if (has_next) load_q(x);
+            continue;
+        }
         if (has_next) load_q(x);   // in flight during the merge
 
         // ---- merge the two groups' partial results.  A wave keeps half of its O^T tiles and hands the
@@ -657,10 +699,10 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
     }
 }
 
-template <int D, bool KV_I8, bool OUT_F32>
+template <int D, bool KV_I8, bool OUT_F32, int MODE = 0>
 static hipError_t launch_one(const PrefillParams& p, hipStream_t stream) {
     const unsigned grid = (unsigned)(8 * p.chunk);
-    hipLaunchKernelGGL((slim_prefill_kernel<D, KV_I8, OUT_F32>), dim3(grid), dim3(kPrefillThreads), 0,
+    hipLaunchKernelGGL((slim_prefill_kernel<D, KV_I8, OUT_F32, MODE>), dim3(grid), dim3(kPrefillThreads), 0,
                        stream, p);
     return hipGetLastError();
 }
@@ -686,6 +728,13 @@ hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream) {
     p.total = a.batch * a.q_heads * p.n_pair;
     p.chunk = (p.total + 7) / 8;
     p.scale_log2e = a.softmax_scale * kLog2e;
+    p.row_max = a.row_max;
+    if (a.row_max) {   // the comparison variant: bf16 K/V only (checked by the caller); two launches
+        hipError_t e = a.head_dim == 128 ? launch_one<128, false, false, 1>(p, stream) : launch_one<64, false, false, 1>(p, stream);
+        if (e != hipSuccess) return e;
+        if (a.head_dim == 128) return a.out_f32 ? launch_one<128, false, true, 2>(p, stream) : launch_one<128, false, false, 2>(p, stream);
+        return a.out_f32 ? launch_one<64, false, true, 2>(p, stream) : launch_one<64, false, false, 2>(p, stream);
+    }
     const int sel = (a.head_dim == 128 ? 4 : 0) | (a.kv_int8 ? 2 : 0) | (a.out_f32 ? 1 : 0);
     switch (sel) {
         case 0: return launch_one<64, false, false>(p, stream);

@@ -26,6 +26,7 @@ struct PrefillArgs {
     int batch, q_heads, kv_heads, seq_len, head_dim, causal;
     float softmax_scale;
     bool kv_int8, out_f32;
+    float* row_max;   // null, or (bf16 K/V only) the two-sweep variant's workspace [batch, q_heads, seq_len, 2]
 };
 hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream);
 

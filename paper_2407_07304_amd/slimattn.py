@@ -41,6 +41,10 @@ def load():
         lib.slim_attn_prefill.restype = i
         lib.slim_attn_prefill_emit_int8.argtypes = [p, p, p, p, p, p, p, p, i, i, i, i, i, i, f, i, p]
         lib.slim_attn_prefill_emit_int8.restype = i
+        lib.slim_attn_prefill_two_sweep_workspace_bytes.argtypes = [i, i, i, i, i]
+        lib.slim_attn_prefill_two_sweep_workspace_bytes.restype = ctypes.c_size_t
+        lib.slim_attn_prefill_two_sweep.argtypes = [p, p, p, p, p, ctypes.c_size_t, i, i, i, i, i, i, f, i, p]
+        lib.slim_attn_prefill_two_sweep.restype = i
         lib.slim_attn_decode_int8_workspace_bytes.argtypes = [i, i, i, i, i]
         lib.slim_attn_decode_int8_workspace_bytes.restype = ctypes.c_size_t
         lib.slim_attn_decode_int8.argtypes = [p, p, p, p, p, p, p, ctypes.c_size_t, i, i, i, i, i, i, f, p]
@@ -183,3 +187,20 @@ def slim_attn_prefill_emit_int8(q, k, v, softmax_scale, causal=True, out=None, o
                                               int(bool(causal)), float(softmax_scale),
                                               SLIM_F32 if out.dtype == torch.float32 else SLIM_BF16, _stream()))
     return out, kc, ks, vc, vs
+
+
+def slim_attn_prefill_two_sweep(q, k, v, softmax_scale, causal=True, out=None, out_dtype=torch.bfloat16, workspace=None):
+    """The two-sweep comparison variant of the bf16 prefill (row maxima first, then everything else)."""
+    B, Hq, S, D = q.shape
+    Hkv = k.shape[1]
+    assert k.shape == (B, Hkv, S, D) and v.shape == k.shape and k.dtype == torch.bfloat16 and v.dtype == torch.bfloat16
+    if out is None:
+        out = torch.empty((B, Hq, S, D), dtype=out_dtype, device=q.device)
+    need = int(load().slim_attn_prefill_two_sweep_workspace_bytes(B, Hq, Hkv, S, D))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    _check(load().slim_attn_prefill_two_sweep(_ptr(q, torch.bfloat16), _ptr(k, torch.bfloat16), _ptr(v, torch.bfloat16),
+                                              _ptr(out), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                              B, Hq, Hkv, S, D, int(bool(causal)), float(softmax_scale),
+                                              SLIM_F32 if out.dtype == torch.float32 else SLIM_BF16, _stream()))
+    return out

@@ -27,7 +27,8 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert {"kv_quant_int8", "slim_attn_prefill", "slim_attn_decode_int8", "slim_attn_decode_int8_varlen",
-            "kv_quant_int8_append", "slim_attn_prefill_emit_int8", "slim_attn_decode_int8_workspace_bytes", "slim_status_string"} <= set(names)
+            "kv_quant_int8_append", "slim_attn_prefill_emit_int8", "slim_attn_decode_int8_workspace_bytes", "slim_status_string",
+            "slim_attn_prefill_two_sweep", "slim_attn_prefill_two_sweep_workspace_bytes"} <= set(names)
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -117,6 +118,22 @@ def test_append_rejects_bad_arguments(lib):
     assert call(T=0) == 2 and call(B=0) == 2
     assert call(D=100) == 3
     assert call(codes=A + 8) == 4 and call(pos=A + 1) == 4
+
+
+def test_prefill_two_sweep_rejects_bad_arguments(lib):
+    f = lib.slim_attn_prefill_two_sweep
+    need = lib.slim_attn_prefill_two_sweep_workspace_bytes(1, 4, 2, 100, 128)
+    assert need == 1 * 4 * 100 * 2 * 4
+    assert lib.slim_attn_prefill_two_sweep_workspace_bytes(1, 4, 3, 100, 128) == 0
+
+    def call(q=A, k=A, v=A, out=A, ws=A, wb=need, S=100, D=128, od=0):
+        return f(P(q), P(k), P(v), P(out), P(ws), wb, 1, 4, 2, S, D, 1, 0.1, od, None)
+
+    assert call(ws=None) == 1 and call(v=None) == 1
+    assert call(S=0) == 2
+    assert call(D=96) == 3 and call(od=7) == 3
+    assert call(ws=A + 4) == 4
+    assert call(wb=need - 1) == 5
 
 
 def test_prefill_emit_rejects_bad_arguments(lib):

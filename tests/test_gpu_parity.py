@@ -69,7 +69,7 @@ def test_kv_quant_bit_exact_c3_shape(sa, oracle):
 
 # ---------------------------------------------------------------- prefill
 
-def _prefill_case(sa, oracle, B, Hq, Hkv, S, D, causal, kv_int8, out_f32, seed, rows=None):
+def _prefill_case(sa, oracle, B, Hq, Hkv, S, D, causal, kv_int8, out_f32, seed, rows=None, two_sweep=False):
     rng = np.random.default_rng(seed)
     q = normal_bf16(rng, (B, Hq, S, D))
     k = normal_bf16(rng, (B, Hkv, S, D))
@@ -84,7 +84,8 @@ def _prefill_case(sa, oracle, B, Hq, Hkv, S, D, causal, kv_int8, out_f32, seed, 
         torch.cuda.synchronize()
         want = oracle.attn(q, kc, vc, scale, causal, k_scale=ks, v_scale=vs, rows=rows)
     else:
-        out = sa.slim_attn_prefill(dev_bf16(q), dev_bf16(k), dev_bf16(v), scale, causal, out_dtype=od)
+        fn = sa.slim_attn_prefill_two_sweep if two_sweep else sa.slim_attn_prefill
+        out = fn(dev_bf16(q), dev_bf16(k), dev_bf16(v), scale, causal, out_dtype=od)
         torch.cuda.synchronize()
         want = oracle.attn(q, k, v, scale, causal, rows=rows)
     got = host_f64(out)
@@ -548,3 +549,37 @@ def test_prefill_that_emits_the_int8_cache(sa, oracle, B, Hq, Hkv, S, D, causal)
     assert np.array_equal(kc.cpu().numpy(), okc) and np.array_equal(vc.cpu().numpy(), ovc)
     assert np.array_equal(ks.cpu().numpy().view(np.uint32), oks.view(np.uint32))
     assert np.array_equal(vs.cpu().numpy().view(np.uint32), ovs.view(np.uint32))
+
+
+# ---------------------------------------------------------------- the two-sweep comparison variant
+
+@pytest.mark.parametrize("B,Hq,Hkv,S,D", SMALL)
+@pytest.mark.parametrize("causal", [True, False])
+def test_prefill_two_sweep_small_shapes(sa, oracle, B, Hq, Hkv, S, D, causal):
+    print("two-sweep prefill", B, Hq, Hkv, S, D, causal, flush=True)
+    _prefill_case(sa, oracle, B, Hq, Hkv, S, D, causal, False, out_f32=(S % 2 == 1), seed=40 + S, two_sweep=True)
+
+
+@pytest.mark.timeout(600)
+def test_prefill_two_sweep_c2_full_size(sa, oracle):
+    w = WORKLOADS["C2"]
+    print("two-sweep prefill C2 (sampled rows of every head)", flush=True)
+    _prefill_case(sa, oracle, w.batch, w.q_heads, w.kv_heads, w.seq_len, w.head_dim, True, False, False, w.seed,
+                  rows=_sample_rows(w.seq_len, 100, 2), two_sweep=True)
+
+
+def test_prefill_two_sweep_large_scores_and_repeats(sa, oracle):
+    # scores far from zero (the first sweep's maxima carry the whole range), run twice into a workspace that
+    # starts dirty: the same bits both times, and the one-sweep kernel's result up to rounding order
+    B, Hq, Hkv, S, D = 1, 4, 2, 700, 128
+    rng = np.random.default_rng(77)
+    q, k, v = normal_bf16(rng, (B, Hq, S, D)), normal_bf16(rng, (B, Hkv, S, D)), normal_bf16(rng, (B, Hkv, S, D))
+    dq, dk, dv = dev_bf16(q), dev_bf16(k), dev_bf16(v)
+    ws = torch.full((B * Hq * S * 2,), float("nan"), dtype=torch.float32, device="cuda")
+    a = sa.slim_attn_prefill_two_sweep(dq, dk, dv, 2.0, True, out_dtype=torch.float32, workspace=ws)
+    b = sa.slim_attn_prefill_two_sweep(dq, dk, dv, 2.0, True, out_dtype=torch.float32, workspace=ws)
+    one = sa.slim_attn_prefill(dq, dk, dv, 2.0, True, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+    check_close(host_f64(a), oracle.attn(q, k, v, 2.0, True), "two-sweep, scale 2")
+    assert (a - one).abs().max().item() <= 2e-2
