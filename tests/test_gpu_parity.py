@@ -402,7 +402,7 @@ def test_decode_per_sequence_lengths(sa, oracle, D, Hq, Hkv):
     torch.cuda.synchronize()
     # (the tolerance is that of an output tensor: max-abs over everything, mean-abs over the batch.  A sequence of
     # one token returns v_0 times its v_scale rounded to bf16 in the grouped-query kernel, a relative error of up
-    # to 2^-9 on every element of that row, so a single short row sits near the mean-abs limit by itself.)
+    # to 2^-8 on every element of that row, so a single short row sits near the mean-abs limit by itself.)
     def expect(lengths):
         return np.concatenate([oracle.attn(q[b:b + 1], kc[b:b + 1, :, :n], vc[b:b + 1, :, :n], scale, False,
                                            k_scale=ks[b:b + 1, :, :n], v_scale=vs[b:b + 1, :, :n])
@@ -583,3 +583,64 @@ def test_prefill_two_sweep_large_scores_and_repeats(sa, oracle):
     assert torch.equal(a, b)
     check_close(host_f64(a), oracle.attn(q, k, v, 2.0, True), "two-sweep, scale 2")
     assert (a - one).abs().max().item() <= 2e-2
+
+
+# ---------------------------------------------------------------- sharp softmax: the arithmetic's own bound
+
+@pytest.mark.parametrize("kv_int8", [False, True])
+@pytest.mark.parametrize("out_f32", [False, True])
+def test_sharp_softmax_stays_within_the_rounding_bound(sa, oracle, kv_int8, out_f32):
+    # scale 0.5 on N(0,1) inputs: most rows are carried by one key, so the rounding of P (INT8: of P * v_scale) to
+    # bf16 is not averaged over the keys.  One rounding to nearest is off by at most 2^-8 relative, hence per element
+    #   |o - o_exact| <= 2^-8 * sum_j p_j |v_j|  (+ 2^-8 |o| for a bf16 output)  + fp32 noise,
+    # the first sum being the oracle's attention over |V|.
+    B, Hq, Hkv, S, D, scale = 2, 8, 2, 700, 128, 0.5
+    rng = np.random.default_rng(321)
+    q, k, v = normal_bf16(rng, (B, Hq, S, D)), normal_bf16(rng, (B, Hkv, S, D)), normal_bf16(rng, (B, Hkv, S, D))
+    od = torch.float32 if out_f32 else torch.bfloat16
+    causal = not out_f32
+    if kv_int8:
+        kc, ks = oracle.kv_quant_int8(k)
+        vc, vs = oracle.kv_quant_int8(v)
+        out = sa.slim_attn_prefill(dev_bf16(q), dev(kc), dev(vc), scale, causal, k_scale=dev(ks), v_scale=dev(vs), out_dtype=od)
+        torch.cuda.synchronize()
+        want = oracle.attn(q, kc, vc, scale, causal, k_scale=ks, v_scale=vs)
+        mass = oracle.attn(q, kc, np.abs(vc), scale, causal, k_scale=ks, v_scale=vs)
+    else:
+        out = sa.slim_attn_prefill(dev_bf16(q), dev_bf16(k), dev_bf16(v), scale, causal, out_dtype=od)
+        torch.cuda.synchronize()
+        want = oracle.attn(q, k, v, scale, causal)
+        mass = oracle.attn(q, k, v & np.uint16(0x7fff), scale, causal)
+    got = host_f64(out)
+    bound = 2.0 ** -8 * mass + (0.0 if out_f32 else 2.0 ** -8 * np.abs(want)) + 1e-5 * (1.0 + mass)
+    err = np.abs(got - want)
+    worst = np.unravel_index(np.argmax(err - bound), err.shape)
+    assert (err <= bound).all(), "element %s: error %.3e above its bound %.3e" % (worst, err[worst], bound[worst])
+    assert float(err.mean()) <= 2e-3
+    # the regime is the intended one: most rows are carried by a single key
+    rows = range(S - 40, S)
+    if kv_int8:
+        tops = [oracle.attn_row_probs(q, kc, vc, scale, causal, 0, 0, i, k_scale=ks, v_scale=vs)[0].max() for i in rows]
+    else:
+        tops = [oracle.attn_row_probs(q, k, v, scale, causal, 0, 0, i)[0].max() for i in rows]
+    assert np.median(tops) > 0.5
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(4, 4), (8, 2)])
+def test_sharp_softmax_decode_stays_within_the_rounding_bound(sa, oracle, Hq, Hkv):
+    # the same bound for the decode kernels (per-head: P * v_scale stays in fp32, only the bf16 output rounds;
+    # grouped query heads: P * v_scale is rounded to bf16 as in the prefill)
+    B, T, D, scale = 3, 1500, 128, 0.5
+    rng = np.random.default_rng(654)
+    q, k, v = normal_bf16(rng, (B, Hq, 1, D)), normal_bf16(rng, (B, Hkv, T, D)), normal_bf16(rng, (B, Hkv, T, D))
+    kc, ks = oracle.kv_quant_int8(k)
+    vc, vs = oracle.kv_quant_int8(v)
+    out = sa.slim_attn_decode_int8(dev_bf16(q), dev(kc), dev(ks), dev(vc), dev(vs), scale)
+    torch.cuda.synchronize()
+    want = oracle.attn(q, kc, vc, scale, False, k_scale=ks, v_scale=vs)
+    mass = oracle.attn(q, kc, np.abs(vc), scale, False, k_scale=ks, v_scale=vs)
+    p_round = 2.0 ** -8 * mass if Hq != Hkv else 0.0
+    bound = p_round + 2.0 ** -8 * np.abs(want) + 1e-5 * (1.0 + mass)
+    err = np.abs(host_f64(out) - want)
+    worst = np.unravel_index(np.argmax(err - bound), err.shape)
+    assert (err <= bound).all(), "element %s: error %.3e above its bound %.3e" % (worst, err[worst], bound[worst])
