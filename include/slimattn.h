@@ -9,6 +9,11 @@
  *                          keys, softmax over the row, row times V), bf16 or INT8 K/V
  *   slim_attn_decode_int8  next-token attention over the INT8 cache (section 2.2)
  *
+ * and, around them, what a serving loop needs: kv_quant_int8_append (one new token per
+ * sequence into the cache), slim_attn_prefill_emit_int8 (prefill that also writes the
+ * cache), slim_attn_decode_int8_varlen (a batch whose caches differ in length), plus
+ * slim_attn_prefill_two_sweep, a comparison variant of the prefill.
+ *
  * Common rules
  *   - Every pointer marked "device" is GPU memory owned by the caller, 16-byte
  *     aligned, densely packed in the stated layout (last index fastest).
