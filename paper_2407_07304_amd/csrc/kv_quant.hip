@@ -10,7 +10,10 @@
 
 namespace slim {
 
-template <int D>
+// STREAM: input and output together are larger than the last-level cache, so the input is read with non-temporal loads (4.3 -> 4.6 TB/s
+// on a 1.6 GB cache, 3.8 -> 4.7 TB/s on 400 MB).  A smaller input may be what the next kernel reads again (the
+// K/V of a prefill): it is left to the caches.
+template <int D, bool STREAM>
 __global__ __launch_bounds__(256) void kv_quant_int8_kernel(const uint16_t* __restrict__ x, int8_t* __restrict__ codes,
                                                             float* __restrict__ scales, long n_rows) {
     constexpr int LPR = D / 8;           // lanes per row
@@ -19,7 +22,8 @@ __global__ __launch_bounds__(256) void kv_quant_int8_kernel(const uint16_t* __re
     const long row0 = (long)blockIdx.x * ROWS + threadIdx.x / LPR;
     const long stride = (long)gridDim.x * ROWS;
     for (long row = row0; row < n_rows; row += stride) {   // rows past the end leave whole row groups idle together
-        const u32x4 raw = *reinterpret_cast<const u32x4*>(x + row * D + lane_in_row * 8);
+        const u32x4* src = reinterpret_cast<const u32x4*>(x + row * D + lane_in_row * 8);
+        const u32x4 raw = STREAM ? __builtin_nontemporal_load(src) : *src;
         u32x2 out2;
         float scale;
         quant_row_piece<LPR>(raw, out2, scale);
@@ -56,12 +60,15 @@ hipError_t launch_kv_quant_int8(const void* x, int8_t* codes, float* scales, lon
     long blocks = (n_rows + rows_per_block - 1) / rows_per_block;
     const long max_blocks = 256L * 64;   // 256 CUs; beyond this the grid-stride loop takes over
     if (blocks > max_blocks) blocks = max_blocks;
-    if (head_dim == 128)
-        hipLaunchKernelGGL(kv_quant_int8_kernel<128>, dim3((unsigned)blocks), dim3(256), 0, stream,
-                           (const uint16_t*)x, codes, scales, n_rows);
-    else
-        hipLaunchKernelGGL(kv_quant_int8_kernel<64>, dim3((unsigned)blocks), dim3(256), 0, stream,
-                           (const uint16_t*)x, codes, scales, n_rows);
+    const bool stream_in = n_rows * head_dim * 3 > (256L << 20);   // input + codes beyond the 256 MB last-level cache
+    const dim3 grid((unsigned)blocks), block(256);
+    if (head_dim == 128) {
+        if (stream_in) hipLaunchKernelGGL((kv_quant_int8_kernel<128, true>), grid, block, 0, stream, (const uint16_t*)x, codes, scales, n_rows);
+        else hipLaunchKernelGGL((kv_quant_int8_kernel<128, false>), grid, block, 0, stream, (const uint16_t*)x, codes, scales, n_rows);
+    } else {
+        if (stream_in) hipLaunchKernelGGL((kv_quant_int8_kernel<64, true>), grid, block, 0, stream, (const uint16_t*)x, codes, scales, n_rows);
+        else hipLaunchKernelGGL((kv_quant_int8_kernel<64, false>), grid, block, 0, stream, (const uint16_t*)x, codes, scales, n_rows);
+    }
     return hipGetLastError();
 }
 

@@ -67,6 +67,19 @@ def test_kv_quant_bit_exact_c3_shape(sa, oracle):
     _quant_both(sa, oracle, normal_bf16(np.random.default_rng(w.seed), (w.batch, w.kv_heads, w.seq_len, w.head_dim)))
 
 
+@pytest.mark.timeout(600)
+@pytest.mark.parametrize("D", [128, 64])
+def test_kv_quant_bit_exact_beyond_the_last_level_cache(sa, oracle, D):
+    # an input of more than 256 MB takes the quantiser's streaming loads: same bits
+    shape = (6, 32, 6000 * 128 // D, D)
+    print("kv_quant", shape, flush=True)
+    base = normal_bf16(np.random.default_rng(33), shape[1:])
+    bits = np.stack([base ^ np.uint16(b * 0x8003 & 0xffff) for b in range(shape[0])])   # other signs and last mantissa bits
+    assert bits.nbytes > (256 << 20)
+    bits[1, 2, 100] = 0
+    _quant_both(sa, oracle, bits)
+
+
 # ---------------------------------------------------------------- prefill
 
 def _prefill_case(sa, oracle, B, Hq, Hkv, S, D, causal, kv_int8, out_f32, seed, rows=None, two_sweep=False):
