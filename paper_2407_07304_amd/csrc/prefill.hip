@@ -32,8 +32,11 @@
 //   - A wave reads its MFMA operands from LDS one matrix phase ahead, each fragment right after
 //     the MFMA that consumed its predecessor: the reads issue in the shadow of the MFMAs and
 //     the softmax phase is pure vector work.
-//   - Under the causal mask a workgroup takes the row-block pair (n-1-x, x) one after the
-//     other, so every workgroup does the same amount of work.
+//   - Under the causal mask a workgroup takes the row-block pair (x, n-1-x) one after the
+//     other, so every workgroup does the same amount of work.  The short block goes first: the
+//     key tiles it read are still in the L2 when the long block starts over at tile 0 (the other
+//     order re-fetched them: 81.5 MB of HBM traffic on B=1, H=32, S=2048 against 67.4 MB now,
+//     which is Q, K, V and O once each).
 #include <type_traits>
 
 #include "slim_common.h"
@@ -246,8 +249,8 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         for (int s = 0; s < KS; ++s) qreg[s] = *reinterpret_cast<const bf16x8*>(qp + 16 * s);
     };
     for (int pass = 0; pass < 2; ++pass) {
-        const int rb = pass == 0 ? p.n_rb - 1 - x : x;
-        if (pass == 1 && rb == p.n_rb - 1 - x) break;   // the middle row block of an odd count
+        const int rb = pass == 0 ? x : p.n_rb - 1 - x;
+        if (pass == 1 && rb == x) break;   // the middle row block of an odd count
         const bool has_next = pass == 0 && x != p.n_rb - 1 - x;
         const int i0 = rb * kBR;
         const int my_q = i0 + 32 * w + l32;             // this lane's query row (may be >= S in the last block)
@@ -599,10 +602,10 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         else run(int_c<1>{});
         if constexpr (MODE == 1) {   // this sweep's result: the row maxima; nothing to merge, nothing to store
             if (hh == 0 && my_q < S) p.row_max[((((long)b * p.Hq + h) * S + my_q) * 2) + grp] = M;
-            if (has_next) load_q(x);
+            if (has_next) load_q(p.n_rb - 1 - x);
             continue;
         }
-        if (has_next) load_q(x);   // in flight during the merge
+        if (has_next) load_q(p.n_rb - 1 - x);   // in flight during the merge
 
         // ---- merge the two groups' partial results.  A wave keeps half of its O^T tiles and hands the
         // other half, with its max and row sum, to its partner (same rows, other group) through LDS.
