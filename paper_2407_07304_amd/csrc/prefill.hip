@@ -157,11 +157,13 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         d_voff[j] = (unsigned)r * ROWB + (unsigned)((pos ^ swz_v(r)) * 16);
     }
     const unsigned smem_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
-    auto dma_tile = [&](const u32x4 rs, const unsigned (&off)[NLD], int t, int lds_off) {
+    auto dma_tile = [&](const u32x4 rs, const unsigned (&off)[NLD], int t, int lds_off, bool wanted = true) {
+        // (a tile that is not wanted is requested past the end of the slab: zeros arrive, no memory is read)
+        const unsigned tbase = wanted ? (unsigned)t * (kBC * ROWB) : (unsigned)S * ROWB;
 #pragma unroll
         for (int j = 0; j < NLD; ++j) {
             const unsigned dst = __builtin_amdgcn_readfirstlane(smem_base + (unsigned)(lds_off + ((kBC / NLD) * j + RPW * w) * ROWL));
-            const unsigned voff = (unsigned)t * (kBC * ROWB) + off[j];
+            const unsigned voff = tbase + off[j];
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
                          :
                          : "s"(dst), "v"(voff), "s"(rs)
@@ -498,18 +500,12 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                int in_flight = 0;   // wave-wide requests of this phase still allowed in flight at its end
                 if constexpr (!KV_I8) {
-                    // K tile phi+6 and V tile phi+4 straight into their ring slots; tiles past the last one
-                    // this row block needs are not requested, so the ring is quiet when the pass ends
-                    if (phi + 6 < n_tiles) {
-                        dma_tile(krs_raw, d_koff, phi + 6, ((phi + 6) & (kRingK - 1)) * TILEB);
-                        in_flight += NLD;
-                    }
-                    if (phi + 4 < n_tiles && !stats_only) {
-                        dma_tile(vrs_raw, d_voff, phi + 4, K_BYTES + P4 * TILEB);
-                        in_flight += NLD;
-                    }
+                    // K tile phi+6 and V tile phi+4 straight into their ring slots.  Always the same number of
+                    // requests, so that the wait at the end of the phase is the same instruction every time:
+                    // past the last tile this row block needs, zeros are requested from beyond the slab.
+                    dma_tile(krs_raw, d_koff, phi + 6, ((phi + 6) & (kRingK - 1)) * TILEB, phi + 6 < n_tiles);
+                    if (!stats_only) dma_tile(vrs_raw, d_voff, phi + 4, K_BYTES + P4 * TILEB, phi + 4 < n_tiles);
                 } else {
                     // the pieces loaded two phases ago go to K tile phi+5 and V tile phi+3
                     store_tile(((phi + 5) & (kRingK - 1)) * TILEBK, p_kdst, sg.k);
@@ -534,9 +530,7 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
                 __builtin_amdgcn_s_setprio(0);
                 if constexpr (!KV_I8) {
                     // what this wave requested in its previous matrix phase is read from the next phase on
-                    if (in_flight == 2 * NLD) __builtin_amdgcn_s_waitcnt(0x0f70 | (2 * NLD));
-                    else if (in_flight == NLD) __builtin_amdgcn_s_waitcnt(0x0f70 | NLD);
-                    else __builtin_amdgcn_s_waitcnt(0x0f70);
+                    __builtin_amdgcn_s_waitcnt(0x0f70 | (stats_only ? NLD : 2 * NLD));
                 } else {
                     load_tile(krs, phi + 7, sg.k);
                     load_tile(vrs, phi + 5, sg.v);
@@ -600,6 +594,12 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         };
         if (grp == 0) run(int_c<0>{});
         else run(int_c<1>{});
+        if constexpr (!KV_I8) {
+            // the last phases' requests (zeros) have landed before the ring is used for anything else
+            __builtin_amdgcn_s_waitcnt(0x0f70);
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+        }
         if constexpr (MODE == 1) {   // this sweep's result: the row maxima; nothing to merge, nothing to store
             if (hh == 0 && my_q < S) p.row_max[((((long)b * p.Hq + h) * S + my_q) * 2) + grp] = M;
             if (has_next) load_q(p.n_rb - 1 - x);
