@@ -171,6 +171,20 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         }
     };
 
+    // The same, one load at a time: the address work first, the request later, so that a matrix phase can tuck
+    // them between its MFMAs without ever keeping the matrix pipe waiting for the next one.
+    auto dma_prep = [&](const unsigned (&off)[NLD], int j, int t, int lds_off, bool wanted, unsigned& dst, unsigned& voff) {
+        const unsigned tbase = wanted ? (unsigned)t * (kBC * ROWB) : (unsigned)S * ROWB;
+        dst = __builtin_amdgcn_readfirstlane(smem_base + (unsigned)(lds_off + ((kBC / NLD) * j + RPW * w) * ROWL));
+        voff = tbase + off[j];
+    };
+    auto dma_fire = [&](const u32x4 rs, unsigned dst, unsigned voff) {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                     :
+                     : "s"(dst), "v"(voff), "s"(rs)
+                     : "memory", "m0");
+    };
+
     // INT8: piece gl + 256 i of thread gl (16 codes) goes through registers and leaves as two bf16 chunks.
     // The last wave of a group also carries the tile's 32 + 32 scales.
     constexpr int CPR = ROWB / 16;            // 16-byte pieces per row in memory
@@ -487,26 +501,35 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
                 __builtin_amdgcn_sched_barrier(0);
+                // bf16: K tile phi+6 and V tile phi+4 go straight into their ring slots, one load per step of
+                // this loop (DT = 2 NLD steps: first the K tile's loads, then the V tile's), the address work
+                // behind the score MFMA and the request behind the P V MFMA.  Always the same number of
+                // requests, so that the wait at the end of the phase is the same instruction every time: past
+                // the last tile this row block needs, zeros are requested from beyond the slab.
+                static_assert(KV_I8 || DT == 2 * NLD, "one ring load per step of the first MFMA loop");
 #pragma unroll
                 for (int i = 0; i < DT; ++i) {
+                    unsigned dma_dst = 0, dma_voff = 0;
                     score_mfma(i, acc);
                     __builtin_amdgcn_sched_barrier(0);
                     fetch_k1(i, k_rd);
+                    if constexpr (!KV_I8) {
+                        if (i < NLD) dma_prep(d_koff, i, phi + 6, ((phi + 6) & (kRingK - 1)) * TILEB, phi + 6 < n_tiles, dma_dst, dma_voff);
+                        else if (!stats_only) dma_prep(d_voff, i - NLD, phi + 4, K_BYTES + P4 * TILEB, phi + 4 < n_tiles, dma_dst, dma_voff);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                     if (!stats_only) {
                         pv_mfma(0, i, pw);
                         __builtin_amdgcn_sched_barrier(0);
                         fetch_v1(0, i, v_rd);
                     }
+                    if constexpr (!KV_I8) {
+                        if (i < NLD) dma_fire(krs_raw, dma_dst, dma_voff);
+                        else if (!stats_only) dma_fire(vrs_raw, dma_dst, dma_voff);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                if constexpr (!KV_I8) {
-                    // K tile phi+6 and V tile phi+4 straight into their ring slots.  Always the same number of
-                    // requests, so that the wait at the end of the phase is the same instruction every time:
-                    // past the last tile this row block needs, zeros are requested from beyond the slab.
-                    dma_tile(krs_raw, d_koff, phi + 6, ((phi + 6) & (kRingK - 1)) * TILEB, phi + 6 < n_tiles);
-                    if (!stats_only) dma_tile(vrs_raw, d_voff, phi + 4, K_BYTES + P4 * TILEB, phi + 4 < n_tiles);
-                } else {
+                if constexpr (KV_I8) {
                     // the pieces loaded two phases ago go to K tile phi+5 and V tile phi+3
                     store_tile(((phi + 5) & (kRingK - 1)) * TILEBK, p_kdst, sg.k);
                     store_tile(((P4 + 3) & 3) * TILEBV, p_vdst, sg.v);
