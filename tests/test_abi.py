@@ -146,3 +146,22 @@ def test_prefill_emit_rejects_bad_arguments(lib):
     assert call(S=0) == 2
     assert call(D=96) == 3 and call(od=7) == 3
     assert call(vc=A + 4) == 4 and call(k=A + 2) == 4
+
+
+def test_binding_fails_loudly_without_the_library(tmp_path, monkeypatch):
+    # no CPU fallback: a missing library is an error, not a slower path
+    from paper_2407_07304_amd import slimattn
+    monkeypatch.setattr(slimattn, "LIB_PATH", str(tmp_path / "libslimattn.so"))
+    monkeypatch.setattr(slimattn, "_lib", None, raising=False)
+    with pytest.raises(ImportError, match="no fallback"):
+        slimattn.load()
+
+
+def test_product_code_does_not_touch_the_oracle():
+    # the oracle is test infrastructure: nothing under the package imports or loads it
+    pkg = os.path.join(os.path.dirname(HEADER), "..", "paper_2407_07304_amd")
+    for root, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(root, f)).read()
+                assert not re.search(r"import\s+oracle|from\s+oracle|oracle[/.]|libslim_oracle|slim_oracle\.", text), f
