@@ -25,7 +25,9 @@
 //     than 2^8), so the rescale runs a few times per row block.
 //   - K/V tiles live in an LDS ring (eight K slots, four V slots).  bf16 tiles are written by the
 //     memory pipe itself (buffer loads with an LDS destination, issued by the group in its
-//     matrix phase, six (K) and four (V) tiles ahead) as unpadded rows whose 16-byte chunks are
+//     matrix phase, six (K) and four (V) tiles ahead, one load between two MFMAs, the same
+//     loads and the same wait in every phase: past the last tile they ask for zeros) as unpadded
+//     rows whose 16-byte chunks are
 //     XOR-swizzled by the row, so both the 128-bit K row reads and the V transpose reads are
 //     free of bank conflicts; INT8 tiles pass through registers, where they are widened, into
 //     padded rows.
