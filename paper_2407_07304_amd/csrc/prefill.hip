@@ -126,6 +126,18 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
     const int l = tid & 63, l32 = l & 31, hh = l >> 5;
     const long kvrow0 = ((long)b * p.Hkv + g) * (long)S;
 
+    // Q^T B-operands of a row block: lane holds row my_q, d = 16 s + 8 hh + [0,8).  The first row block's are
+    // requested here, ahead of the address tables below: they come from cold memory.
+    bf16x8 qreg[KS];
+    auto load_q = [&](int rb_q) {
+        const int q_row = min(rb_q * kBR + 32 * w + l32, S - 1);
+        const uint16_t* qp = p.q + (((long)b * p.Hq + h) * S + q_row) * (long)D + 8 * hh;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) qreg[s] = *reinterpret_cast<const bf16x8*>(qp + 16 * s);
+    };
+    load_q(x);
+    __builtin_amdgcn_sched_barrier(0);
+
     // ---- staging.  The buffer descriptors cover exactly this head's K (V) slab: pieces past the end of
     // the sequence read as zero (those keys are masked in the softmax).  A tile is staged by the four
     // waves of ONE group.
@@ -244,7 +256,6 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         float s;
     };
 
-    bf16x8 qreg[KS];
     f32x16 o[DT];
     // LDS read addresses (bytes).  K fragment of k-step s: row l32, chunk 2 s + hh.  V transpose read: the
     // 16 lanes of a group fetch rows k..k+3 (4 lanes per row, 8 bytes each) and lane i of the group
@@ -259,13 +270,6 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
             v_addr[dt] = K_BYTES + rv * ROWLV + (((4 * dt + 2 * ((l >> 4) & 1) + ((l & 3) >> 1)) ^ swz_v(rv)) * 16) + 8 * (l & 1);
     }
 
-    // Q^T B-operands of a row block: lane holds row my_q, d = 16 s + 8 hh + [0,8)
-    auto load_q = [&](int rb_q) {
-        const int q_row = min(rb_q * kBR + 32 * w + l32, S - 1);
-        const uint16_t* qp = p.q + (((long)b * p.Hq + h) * S + q_row) * (long)D + 8 * hh;
-#pragma unroll
-        for (int s = 0; s < KS; ++s) qreg[s] = *reinterpret_cast<const bf16x8*>(qp + 16 * s);
-    };
     for (int pass = 0; pass < 2; ++pass) {
         const int rb = pass == 0 ? x : p.n_rb - 1 - x;
         if (pass == 1 && rb == x) break;   // the middle row block of an odd count
@@ -281,7 +285,7 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         const int t_last = wave_q_lo >= S ? -1 : (p.causal ? min(n_tiles - 1, wave_q_lo / kBC) : n_tiles - 1);
         const int lim = p.causal ? min(my_q, S - 1) : S - 1;   // last key this lane's row may see
 
-        if (pass == 0) load_q(rb);   // (the second pass's Q is requested before the first one's merge)
+        // (the first pass's Q was requested at the top of the kernel, the second pass's is before the first one's merge)
         float M = kMasked, lsum = 0.0f;   // running max in scaled (log2) units; per-lane partial row sum
 
         // ---- prologue.  In the steady state a group stages in its matrix phase phi: bf16 requests K tile
