@@ -79,7 +79,6 @@ using int_c = std::integral_constant<int, N>;
 template <int D, bool KV_I8, bool OUT_F32, int MODE = 0>
 __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const PrefillParams p) {
     static_assert(!(MODE != 0 && KV_I8), "the two-sweep variant exists for bf16 K/V only");
-    constexpr bool TWO_SWEEP = MODE != 0;
     constexpr bool stats_only = MODE == 1;
     constexpr int KS = D / 16;       // k-steps of the score MFMA
     constexpr int DT = D / 32;       // 32-row tiles of O^T
