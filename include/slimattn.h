@@ -22,8 +22,14 @@
  *     state between calls.
  *   - Every call returns a SLIM_* status.  On any status other than SLIM_OK and
  *     SLIM_ERR_LAUNCH nothing was enqueued.  Nothing throws across this boundary.
- *   - bf16 = upper 16 bits of IEEE fp32.  NaN or infinity in an input gives undefined
- *     values in the outputs that depend on it (inputs are not scanned).
+ *   - bf16 = upper 16 bits of IEEE fp32.  Inputs are not scanned for NaN or infinity.  In the
+ *     quantiser a non-finite value makes the codes and the scale of its own row undefined.  In the
+ *     attention calls a non-finite value anywhere in a (batch, KV head)'s K, V or scales may make
+ *     every output row of the query heads that read that KV head undefined, rows that the causal
+ *     mask hides it from included: a masked key takes part in the matrix products with
+ *     probability zero, and zero times infinity is not zero.
+ *   - SLIM_ERR_LAUNCH reports a launch of the call that returns it: an error that an earlier HIP
+ *     call of the thread left behind is dropped before the first launch.
  *   - Query head h reads KV head h / (q_heads / kv_heads): consecutive query heads
  *     share a KV head.
  */
@@ -57,7 +63,9 @@ enum { SLIM_BF16 = 0, SLIM_F32 = 1, SLIM_I8 = 2 };
  * x_bf16  device, in   [batch, kv_heads, seq_len, head_dim] bf16
  * codes   device, out  [batch, kv_heads, seq_len, head_dim] int8
  * scales  device, out  [batch, kv_heads, seq_len] fp32
- * q_heads, causal and softmax_scale belong to the common argument tail and are ignored.
+ * q_heads, causal and softmax_scale belong to the common argument tail: the result does not depend
+ * on them, but they are checked for range like everywhere else (q_heads a positive multiple of
+ * kv_heads, causal 0 or 1, softmax_scale finite and > 0; SLIM_ERR_SHAPE otherwise).
  */
 int kv_quant_int8(const void* x_bf16, int8_t* codes, float* scales,
                   int batch, int q_heads, int kv_heads, int seq_len, int head_dim,
@@ -74,7 +82,7 @@ int kv_quant_int8(const void* x_bf16, int8_t* codes, float* scales,
  * positions   device, in      [batch] int32, 4-byte aligned; a sequence whose position lies
  *             outside [0, kv_len) is skipped (the positions live on the device, so the
  *             library cannot reject them without waiting for the stream).
- * q_heads, causal and softmax_scale belong to the common argument tail and are ignored.
+ * q_heads, causal and softmax_scale: unused but checked for range, as in kv_quant_int8.
  */
 int kv_quant_int8_append(const void* x_new_bf16, int8_t* codes, float* scales, const int32_t* positions,
                          int batch, int q_heads, int kv_heads, int kv_len, int head_dim,

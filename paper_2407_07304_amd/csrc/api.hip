@@ -10,6 +10,19 @@ namespace {
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
+// hipGetLastError() returns (and clears) whatever error an earlier HIP call of this thread left behind, the
+// caller's own included.  Every entry point drops that before its first launch, so that SLIM_ERR_LAUNCH only
+// ever reports a launch of the call that returns it.
+inline void drop_stale_hip_error() { (void)hipGetLastError(); }
+
+// The scalars of the common argument tail that an operation does not use are still checked for range.
+inline int check_unused_tail(int q_heads, int kv_heads, int causal, float softmax_scale) {
+    if (q_heads <= 0 || kv_heads <= 0 || q_heads % kv_heads != 0) return SLIM_ERR_SHAPE;
+    if (causal != 0 && causal != 1) return SLIM_ERR_SHAPE;
+    if (!(softmax_scale > 0.0f) || !isfinite(softmax_scale)) return SLIM_ERR_SHAPE;
+    return SLIM_OK;
+}
+
 // Total element counts must stay indexable with the 32-bit row counters the kernels use.
 inline bool too_large(long a, long b, long c) {
     const long lim = 2147483647L;
@@ -48,14 +61,14 @@ const char* slim_status_string(int status) {
 
 int kv_quant_int8(const void* x_bf16, int8_t* codes, float* scales, int batch, int q_heads, int kv_heads, int seq_len,
                   int head_dim, int causal, float softmax_scale, void* stream) {
-    (void)q_heads;
-    (void)causal;
-    (void)softmax_scale;
     if (!x_bf16 || !codes || !scales) return SLIM_ERR_NULL;
     const int st = check_shape(batch, kv_heads, kv_heads, seq_len, head_dim);
     if (st != SLIM_OK) return st;
+    const int st_tail = check_unused_tail(q_heads, kv_heads, causal, softmax_scale);
+    if (st_tail != SLIM_OK) return st_tail;
     if (misaligned(x_bf16) || misaligned(codes) || misaligned(scales)) return SLIM_ERR_ALIGN;
     const long n_rows = (long)batch * kv_heads * seq_len;
+    drop_stale_hip_error();
     const hipError_t e = slim::launch_kv_quant_int8(x_bf16, codes, scales, n_rows, head_dim, (hipStream_t)stream);
     return e == hipSuccess ? SLIM_OK : SLIM_ERR_LAUNCH;
 }
@@ -63,14 +76,14 @@ int kv_quant_int8(const void* x_bf16, int8_t* codes, float* scales, int batch, i
 int kv_quant_int8_append(const void* x_new_bf16, int8_t* codes, float* scales, const int32_t* positions, int batch,
                          int q_heads, int kv_heads, int kv_len, int head_dim, int causal, float softmax_scale,
                          void* stream) {
-    (void)q_heads;
-    (void)causal;
-    (void)softmax_scale;
     if (!x_new_bf16 || !codes || !scales || !positions) return SLIM_ERR_NULL;
     const int st = check_shape(batch, kv_heads, kv_heads, kv_len, head_dim);
     if (st != SLIM_OK) return st;
+    const int st_tail = check_unused_tail(q_heads, kv_heads, causal, softmax_scale);
+    if (st_tail != SLIM_OK) return st_tail;
     if (misaligned(x_new_bf16) || misaligned(codes) || misaligned(scales)) return SLIM_ERR_ALIGN;
     if ((uintptr_t)positions & 3u) return SLIM_ERR_ALIGN;
+    drop_stale_hip_error();
     const hipError_t e = slim::launch_kv_quant_int8_append(x_new_bf16, codes, scales, positions, batch, kv_heads, kv_len,
                                                            head_dim, (hipStream_t)stream);
     return e == hipSuccess ? SLIM_OK : SLIM_ERR_LAUNCH;
@@ -114,6 +127,7 @@ static int prefill_common(const void* q_bf16, const void* k, const void* v, cons
     a.kv_int8 = kv_dtype == SLIM_I8;
     a.out_f32 = out_dtype == SLIM_F32;
     a.row_max = row_max;
+    drop_stale_hip_error();
     const hipError_t e = slim::launch_prefill(a, (hipStream_t)stream);
     return e == hipSuccess ? SLIM_OK : SLIM_ERR_LAUNCH;
 }
@@ -183,6 +197,7 @@ static int decode_common(const void* q_bf16, const int8_t* k_codes, const float*
     a.kv_len = kv_len;
     a.head_dim = head_dim;
     a.softmax_scale = softmax_scale;
+    drop_stale_hip_error();
     const hipError_t e = slim::launch_decode(a, (hipStream_t)stream);
     return e == hipSuccess ? SLIM_OK : SLIM_ERR_LAUNCH;
 }

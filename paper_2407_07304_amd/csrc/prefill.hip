@@ -511,7 +511,15 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
                 // behind the score MFMA and the request behind the P V MFMA.  Always the same number of
                 // requests, so that the wait at the end of the phase is the same instruction every time: past
                 // the last tile this row block needs, zeros are requested from beyond the slab.
+                // Invariant the hand-written wait below rests on: a matrix phase issues exactly REQ ring requests
+                // (steps i < NLD of the loop: the K tile's, the remaining DT - NLD steps: the V tile's, none of
+                // those in the maxima-only sweep), buffer loads complete in the order they were issued, and the
+                // requests of the wave's PREVIOUS matrix phase are the ones that must have landed.  So the wait
+                // at the end of the phase is vmcnt(REQ): everything but this phase's own requests.
+                constexpr int REQ = KV_I8 ? 0 : NLD + (stats_only ? 0 : DT - NLD);
                 static_assert(KV_I8 || DT == 2 * NLD, "one ring load per step of the first MFMA loop");
+                static_assert(KV_I8 || REQ == (stats_only ? NLD : 2 * NLD), "requests per matrix phase");
+                static_assert(REQ < 16, "vmcnt is written into the low four bits of the wait's immediate");
 #pragma unroll
                 for (int i = 0; i < DT; ++i) {
                     unsigned dma_dst = 0, dma_voff = 0;
@@ -558,7 +566,7 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
                 __builtin_amdgcn_s_setprio(0);
                 if constexpr (!KV_I8) {
                     // what this wave requested in its previous matrix phase is read from the next phase on
-                    __builtin_amdgcn_s_waitcnt(0x0f70 | (stats_only ? NLD : 2 * NLD));
+                    __builtin_amdgcn_s_waitcnt(0x0f70 | REQ);   // vmcnt(REQ), see the invariant above
                 } else {
                     load_tile(krs, phi + 7, sg.k);
                     load_tile(vrs, phi + 5, sg.v);

@@ -75,6 +75,12 @@ def test_quant_rejects_bad_arguments(lib):
     assert f(P(A), P(A), P(A), 1, 1, 1, 0, 128, 0, 1.0, None) == 2
     assert f(P(A), P(A), P(A), 1, 1, 1, 4, 100, 0, 1.0, None) == 3
     assert f(P(A), P(A + 1), P(A), 1, 1, 1, 4, 128, 0, 1.0, None) == 4
+    # the scalars of the common tail that the quantiser does not use are still checked for range
+    assert f(P(A), P(A), P(A), 1, 0, 1, 4, 128, 0, 1.0, None) == 2
+    assert f(P(A), P(A), P(A), 1, 3, 2, 4, 128, 0, 1.0, None) == 2
+    assert f(P(A), P(A), P(A), 1, 1, 1, 4, 128, 2, 1.0, None) == 2
+    assert f(P(A), P(A), P(A), 1, 1, 1, 4, 128, 0, 0.0, None) == 2
+    assert f(P(A), P(A), P(A), 1, 1, 1, 4, 128, 0, float("nan"), None) == 2
 
 
 def test_decode_rejects_bad_arguments_and_reports_workspace(lib):
@@ -111,13 +117,14 @@ def test_varlen_decode_rejects_bad_arguments(lib):
 def test_append_rejects_bad_arguments(lib):
     f = lib.kv_quant_int8_append
 
-    def call(x=A, codes=A, scales=A, pos=A, B=2, Hkv=2, T=100, D=128):
-        return f(P(x), P(codes), P(scales), P(pos), B, 1, Hkv, T, D, 0, 1.0, None)
+    def call(x=A, codes=A, scales=A, pos=A, B=2, Hq=2, Hkv=2, T=100, D=128, causal=0, scale=1.0):
+        return f(P(x), P(codes), P(scales), P(pos), B, Hq, Hkv, T, D, causal, scale, None)
 
     assert call(x=None) == 1 and call(pos=None) == 1 and call(scales=None) == 1
     assert call(T=0) == 2 and call(B=0) == 2
     assert call(D=100) == 3
     assert call(codes=A + 8) == 4 and call(pos=A + 1) == 4
+    assert call(Hq=3) == 2 and call(causal=-1) == 2 and call(scale=float("inf")) == 2
 
 
 def test_prefill_two_sweep_rejects_bad_arguments(lib):
