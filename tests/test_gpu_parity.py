@@ -547,20 +547,25 @@ def test_a_stale_hip_error_is_not_reported_as_a_failed_launch(sa, oracle):
     ref = sa.slim_attn_decode_int8(q, kc, ks, vc, vs, scale)
     torch.cuda.synchronize()
     hip = _loaded_hip_runtime()
+    # everything torch has to launch or allocate comes first: torch checks for left-over errors itself
+    kc2, ks2, out = torch.zeros_like(kc), torch.zeros_like(ks), torch.zeros_like(ref)
+    qp, kp, vp = (t[:, :, :300].contiguous() for t in (k, k, v))
+    pre = torch.zeros_like(qp)
+    ws = torch.zeros((sa.slim_attn_decode_int8_workspace_bytes(B, Hq, Hkv, T, D),), dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
 
     def plant():
         assert hip.hipSetDevice(12345) != 0   # an invalid device: fails, changes nothing, leaves its error behind
 
     plant()
-    kc2, ks2 = sa.kv_quant_int8(k)
+    sa.kv_quant_int8(k, kc2, ks2)
     plant()
-    out = torch.zeros_like(ref)
-    sa.slim_attn_decode_int8(q, kc, ks, vc, vs, scale, out=out)   # split kernel + combine kernel
+    sa.slim_attn_decode_int8(q, kc, ks, vc, vs, scale, out=out, workspace=ws)   # split kernel + combine kernel
     plant()
-    pre = sa.slim_attn_prefill(k[:, :, :300].contiguous(), k[:, :, :300].contiguous(), v[:, :, :300].contiguous(), scale, True)
+    sa.slim_attn_prefill(qp, kp, vp, scale, True, out=pre)
     torch.cuda.synchronize()
     assert torch.equal(kc2, kc) and torch.equal(ks2, ks) and torch.equal(out, ref)
-    assert bool(torch.isfinite(pre).all())
+    assert bool(torch.isfinite(pre).all()) and bool((pre != 0).any())
     hip.hipGetLastError()
 
 
