@@ -19,7 +19,7 @@
  *     aligned, densely packed in the stated layout (last index fastest).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is
  *     enqueued on it; no call synchronises, allocates or frees, and the library keeps no
- *     state between calls.
+ *     state between calls (slim_attn_decode_int8_static alone owns a static device array).
  *   - Every call returns a SLIM_* status.  On any status other than SLIM_OK and
  *     SLIM_ERR_LAUNCH nothing was enqueued.  Nothing throws across this boundary.
  *   - bf16 = upper 16 bits of IEEE fp32.  Inputs are not scanned for NaN or infinity.  In the
@@ -172,6 +172,24 @@ int slim_attn_decode_int8(const void* q_bf16, const int8_t* k_codes, const float
                           void* workspace, size_t workspace_bytes,
                           int batch, int q_heads, int kv_heads, int kv_len, int head_dim,
                           int causal, float softmax_scale, void* stream);
+
+/*
+ * slim_attn_decode_int8 for callers that cannot provide or allocate a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without the workspace,
+ * same kernels, same result bit for bit; the partial results of the key-axis splits go to a static device
+ * array of slim_attn_decode_int8_static_max_bytes() bytes (16 MiB) that is part of the library's code object:
+ * every GPU the library runs on holds its own copy until the process ends.  The call allocates and frees
+ * nothing; its first call on a device looks up that device's address of the array (make that call outside a
+ * graph capture).  A shape whose slim_attn_decode_int8_workspace_bytes() exceeds the array returns
+ * SLIM_ERR_WORKSPACE and enqueues nothing.  All calls on one GPU share the array: two such calls that may run
+ * at the same time there (different streams, different threads) race on it; calls on one stream are safe,
+ * and nothing in the array has to be cleared between calls (every record that is read is written first).
+ */
+size_t slim_attn_decode_int8_static_max_bytes(void);
+int slim_attn_decode_int8_static(const void* q_bf16, const int8_t* k_codes, const float* k_scale,
+                                 const int8_t* v_codes, const float* v_scale, void* out_bf16,
+                                 int batch, int q_heads, int kv_heads, int kv_len, int head_dim,
+                                 int causal, float softmax_scale, void* stream);
 
 /*
  * The same decode step for a batch whose sequences have caches of different lengths

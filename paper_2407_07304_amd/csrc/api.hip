@@ -168,11 +168,15 @@ size_t slim_attn_decode_int8_workspace_bytes(int batch, int q_heads, int kv_head
     return slim::decode_workspace_bytes(batch, q_heads, kv_heads, kv_len, head_dim);
 }
 
+constexpr size_t kUseStaticScratch = ~(size_t)0;   // decode_common: workspace == NULL with this size selects the static array
+
 static int decode_common(const void* q_bf16, const int8_t* k_codes, const float* k_scale, const int8_t* v_codes,
                          const float* v_scale, const int32_t* kv_lens, void* out_bf16, void* workspace,
                          size_t workspace_bytes, int batch, int q_heads, int kv_heads, int kv_len, int head_dim, int causal,
                          float softmax_scale, void* stream) {
-    if (!q_bf16 || !k_codes || !k_scale || !v_codes || !v_scale || !out_bf16 || !workspace) return SLIM_ERR_NULL;
+    // use_static: the partial results go to the library's own static device array instead of a caller's workspace
+    const bool use_static = workspace == nullptr && workspace_bytes == kUseStaticScratch;
+    if (!q_bf16 || !k_codes || !k_scale || !v_codes || !v_scale || !out_bf16 || (!workspace && !use_static)) return SLIM_ERR_NULL;
     const int st = check_shape(batch, q_heads, kv_heads, kv_len, head_dim);
     if (st != SLIM_OK) return st;
     if (causal != 0 && causal != 1) return SLIM_ERR_SHAPE;
@@ -181,7 +185,15 @@ static int decode_common(const void* q_bf16, const int8_t* k_codes, const float*
         misaligned(v_scale) || misaligned(out_bf16) || misaligned(workspace))
         return SLIM_ERR_ALIGN;
     if (kv_lens && ((uintptr_t)kv_lens & 3u)) return SLIM_ERR_ALIGN;
-    if (workspace_bytes < slim::decode_workspace_bytes(batch, q_heads, kv_heads, kv_len, head_dim)) return SLIM_ERR_WORKSPACE;
+    const size_t need = slim::decode_workspace_bytes(batch, q_heads, kv_heads, kv_len, head_dim);
+    if (use_static) {
+        if (need > slim::kDecodeStaticScratchBytes) return SLIM_ERR_WORKSPACE;
+        float* own = nullptr;
+        if (slim::decode_static_scratch(&own) != hipSuccess) return SLIM_ERR_LAUNCH;
+        workspace = own;
+    } else if (workspace_bytes < need) {
+        return SLIM_ERR_WORKSPACE;
+    }
     slim::DecodeArgs a;
     a.q = q_bf16;
     a.k_codes = k_codes;
@@ -207,6 +219,15 @@ int slim_attn_decode_int8(const void* q_bf16, const int8_t* k_codes, const float
                           int q_heads, int kv_heads, int kv_len, int head_dim, int causal, float softmax_scale,
                           void* stream) {
     return decode_common(q_bf16, k_codes, k_scale, v_codes, v_scale, nullptr, out_bf16, workspace, workspace_bytes, batch,
+                         q_heads, kv_heads, kv_len, head_dim, causal, softmax_scale, stream);
+}
+
+size_t slim_attn_decode_int8_static_max_bytes(void) { return slim::kDecodeStaticScratchBytes; }
+
+int slim_attn_decode_int8_static(const void* q_bf16, const int8_t* k_codes, const float* k_scale, const int8_t* v_codes,
+                                 const float* v_scale, void* out_bf16, int batch, int q_heads, int kv_heads, int kv_len,
+                                 int head_dim, int causal, float softmax_scale, void* stream) {
+    return decode_common(q_bf16, k_codes, k_scale, v_codes, v_scale, nullptr, out_bf16, nullptr, kUseStaticScratch, batch,
                          q_heads, kv_heads, kv_len, head_dim, causal, softmax_scale, stream);
 }
 

@@ -17,6 +17,7 @@
 //     exchange of the chunk's probabilities;
 //   - slots and waves are merged in LDS at the end, and a second kernel merges the splits
 //     in a fixed order (no atomics: the result does not depend on arrival order).
+#include <mutex>
 #include <type_traits>
 
 #include "slim_common.h"
@@ -276,6 +277,31 @@ size_t decode_workspace_bytes(int batch, int q_heads, int kv_heads, int kv_len, 
                                                                   : decode_num_splits(kv_len, (long)batch * q_heads);
     const size_t n = (size_t)batch * q_heads * n_split;
     return n * ((size_t)head_dim + 2) * sizeof(float);
+}
+
+// Scratch of the decode entry point that may not allocate: the same (max, sum, accumulator) partials as the
+// caller-owned workspace, in one array per GPU that lives as long as the process.  In host code the array's
+// name only stands for the symbol: its device address is asked for once per device and kept.
+static __device__ __align__(256) unsigned char scratch[kDecodeStaticScratchBytes];
+
+hipError_t decode_static_scratch(float** ptr) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void* per_device[kMaxDevices] = {};
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (per_device[dev] == nullptr) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // this device's copy of the array
+        if (e != hipSuccess) return e;
+        if (p == nullptr) return hipErrorInvalidSymbol;
+        per_device[dev] = p;
+    }
+    *ptr = static_cast<float*>(per_device[dev]);
+    return hipSuccess;
 }
 
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t stream) {

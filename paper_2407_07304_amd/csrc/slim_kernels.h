@@ -54,5 +54,9 @@ int decode_gqa_num_splits(int kv_len, long n_bg);
 hipError_t launch_decode_gqa_split(const DecodeArgs& a, float* ws_acc, float* ws_ml, int n_split, hipStream_t stream);
 size_t decode_workspace_bytes(int batch, int q_heads, int kv_heads, int kv_len, int head_dim);
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t stream);
+// The library's own decode scratch (one static device array per GPU) for the entry point that may not
+// allocate: its address on the current device, looked up on the first call there.
+constexpr size_t kDecodeStaticScratchBytes = (size_t)16 << 20;
+hipError_t decode_static_scratch(float** ptr);
 
 }  // namespace slim

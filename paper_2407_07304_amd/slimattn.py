@@ -49,6 +49,10 @@ def load():
         lib.slim_attn_decode_int8_workspace_bytes.restype = ctypes.c_size_t
         lib.slim_attn_decode_int8.argtypes = [p, p, p, p, p, p, p, ctypes.c_size_t, i, i, i, i, i, i, f, p]
         lib.slim_attn_decode_int8.restype = i
+        lib.slim_attn_decode_int8_static_max_bytes.argtypes = []
+        lib.slim_attn_decode_int8_static_max_bytes.restype = ctypes.c_size_t
+        lib.slim_attn_decode_int8_static.argtypes = [p, p, p, p, p, p, i, i, i, i, i, i, f, p]
+        lib.slim_attn_decode_int8_static.restype = i
         lib.slim_attn_decode_int8_varlen.argtypes = [p, p, p, p, p, p, p, p, ctypes.c_size_t, i, i, i, i, i, i, f, p]
         lib.slim_attn_decode_int8_varlen.restype = i
         lib.slim_status_string.argtypes = [i]
@@ -132,6 +136,25 @@ def slim_attn_decode_int8(q, k_codes, k_scale, v_codes, v_scale, softmax_scale, 
                                         _ptr(v_codes, torch.int8), _ptr(v_scale, torch.float32),
                                         _ptr(out, torch.bfloat16), _ptr(workspace), workspace.numel() * workspace.element_size(),
                                         B, Hq, Hkv, T, D, int(bool(causal)), float(softmax_scale), _stream()))
+    return out
+
+
+def slim_attn_decode_int8_static_max_bytes() -> int:
+    return int(load().slim_attn_decode_int8_static_max_bytes())
+
+
+def slim_attn_decode_int8_static(q, k_codes, k_scale, v_codes, v_scale, softmax_scale, out, causal=False):
+    """slim_attn_decode_int8 with the library's own static scratch array: no workspace argument, and nothing is
+    allocated here either, so the caller passes ``out`` [B,Hq,1,D] bf16."""
+    B, Hq, one, D = q.shape
+    assert one == 1
+    Hkv, T = k_codes.shape[1], k_codes.shape[2]
+    assert k_codes.shape == (B, Hkv, T, D) and v_codes.shape == k_codes.shape
+    assert k_scale.shape == (B, Hkv, T) and v_scale.shape == (B, Hkv, T) and out.shape == (B, Hq, 1, D)
+    _check(load().slim_attn_decode_int8_static(_ptr(q, torch.bfloat16), _ptr(k_codes, torch.int8),
+                                               _ptr(k_scale, torch.float32), _ptr(v_codes, torch.int8),
+                                               _ptr(v_scale, torch.float32), _ptr(out, torch.bfloat16), B, Hq, Hkv, T, D,
+                                               int(bool(causal)), float(softmax_scale), _stream()))
     return out
 
 
