@@ -9,8 +9,13 @@ One step = one pass of the whole path over seeded synthetic inputs already resid
 `value` is the prefill throughput in TFLOP/s (causal flop count) and `decode.value` the
 decode throughput in GB/s (algorithmic bytes), each from HIP-event timing of its own
 kernel(s) inside the timed steps.  Prints ONE JSON line.
+
+`--probe ceilings` runs the measurement kernels of include/slimprobe.h instead (streaming read, the quantiser's
+traffic without arithmetic, back-to-back MFMAs and the prefill kernel on operands of different bit activity) and
+prints their JSON line: the machine's practical ceilings, measured by the harness that measures the kernels.
 """
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -23,22 +28,56 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBPS = 8000.0      # MI355X HBM3E
+TRAFFIC_PROFILE = os.path.join("profiles", "traffic_fetch_write_c2_c4.txt")
 
-PAPER_TABLE3_MS = {2048: 96.65, 4096: 392.80}   # SlimAttention, 1 socket Xeon 8563C (paper Table 3); context only
 
-
-def measured_traffic():
-    """HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary, or {}."""
-    path = os.path.join(ROOT, "profiles", "traffic_fetch_write_c2_c4.txt")
+def paper_table3_ms():
+    """SlimAttention column of the paper's Table 3 (1 socket Xeon 8563C), from the golden fixture; context only."""
     out = {}
     try:
-        for ln in open(path):
-            if ln.startswith("traffic_bytes "):
-                _, key, val = ln.split()
-                out[key] = int(float(val))
+        for ln in open(os.path.join(ROOT, "tests", "golden", "table3_slimattention_ms.txt")):
+            if ln.strip() and not ln.startswith("#"):
+                s, _, slim = ln.split()
+                out[int(s)] = float(slim)
     except OSError:
         pass
     return out
+
+
+def kernel_sources_sha256():
+    """Hash of the HIP sources the loaded library was built from (the tree's, built in place)."""
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2407_07304_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(d, name), "rb").read())
+    return h.hexdigest()
+
+
+def profiled_traffic():
+    """HBM bytes per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary.  The counters are not
+    read in this run: the figures are those of the profile, and they are only passed on while the profile names
+    the kernel sources this tree holds."""
+    out = {"bytes": {}, "sha": None}
+    try:
+        for ln in open(os.path.join(ROOT, TRAFFIC_PROFILE)):
+            if ln.startswith("traffic_bytes "):
+                _, key, val = ln.split()
+                out["bytes"][key] = int(float(val))
+            elif ln.startswith("sources_sha256 "):
+                out["sha"] = ln.split()[1]
+    except OSError:
+        pass
+    out["current"] = out["sha"] is not None and out["sha"] == kernel_sources_sha256()
+    return out
+
+
+def traffic_fields(prof, key):
+    return {"traffic": prof["bytes"].get(key) if prof["current"] else None,
+            "traffic_source": {"file": TRAFFIC_PROFILE, "measured_in_this_run": False,
+                               "profile_matches_these_kernel_sources": prof["current"],
+                               "profiled_bytes": prof["bytes"].get(key)}}
 
 
 def _cpu_model():
@@ -52,6 +91,105 @@ def _cpu_model():
     return "unknown"
 
 
+def _sample_rows(S, n, seed):
+    rng = np.random.default_rng(seed)
+    fixed = [0, 1, 127, 128, S // 2, S - 129, S - 1]
+    return np.array(sorted(set(fixed + rng.integers(0, S, n).tolist())), dtype=np.int32)
+
+
+def median_ms(torch, fn, iters, warm=3, between=None):
+    """Median and mean HIP-event time of fn() over iters launches on the current stream."""
+    for _ in range(warm):
+        fn()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    for a, b in evs:
+        if between is not None:
+            between()
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    t = np.array([a.elapsed_time(b) for a, b in evs])
+    return float(np.median(t)), float(t.mean()), float(t.min())
+
+
+def probe_ceilings(args):
+    import torch
+    from paper_2407_07304_amd import probes, slimattn as sa
+    from paper_2407_07304_amd import accounting as acct
+    from paper_2407_07304_amd.inputs import normal_bf16
+    sa.load()
+    probes.load()
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    torch.cuda.set_device(0)
+    rng = np.random.default_rng(7)
+    out = {"probe": "ceilings", "device": torch.cuda.get_device_name(0),
+           "peaks": {"bf16_mfma_TFLOPs": PEAK_BF16_TFLOPS, "hbm_GBps": PEAK_HBM_GBPS}}
+
+    def dev_bf16(bits):
+        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+    # ---- 1. plain streaming read of 1 GiB (about the bytes of one C4 decode step)
+    src = torch.randint(0, 255, (1 << 30,), dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    med, mean, mn = median_ms(torch, lambda: probes.slim_probe_stream_read(src, sink), 30)
+    out["stream_read"] = {"bytes": 1 << 30, "ms_median": round(med, 4), "ms_min": round(mn, 4),
+                          "GBps": round((1 << 30) / med / 1e6, 1), "frac_of_hbm_peak": round((1 << 30) / med / 1e6 / PEAK_HBM_GBPS, 4)}
+    del src
+
+    # ---- 2. the quantiser's stream (K of the C4 cache before quantisation: 1.07 GB in, 0.54 GB out) without and
+    # with its arithmetic
+    x = torch.randn((16, 32, 8192, 128), device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    codes = torch.empty(x.shape, dtype=torch.int8, device="cuda")
+    scales = torch.empty(x.shape[:-1], dtype=torch.float32, device="cuda")
+    qbytes = acct.kv_quant_bytes(x.numel() // 128, 128)
+    med, _, mn = median_ms(torch, lambda: probes.slim_probe_quant_traffic(x, codes, scales), 30)
+    out["quant_traffic_only"] = {"bytes": qbytes, "ms_median": round(med, 4), "ms_min": round(mn, 4), "GBps": round(qbytes / med / 1e6, 1)}
+    med, _, mn = median_ms(torch, lambda: sa.kv_quant_int8(x, codes, scales), 30)
+    out["kv_quant_int8_same_stream"] = {"bytes": qbytes, "ms_median": round(med, 4), "ms_min": round(mn, 4), "GBps": round(qbytes / med / 1e6, 1),
+                                        "frac_of_hbm_peak": round(qbytes / med / 1e6 / PEAK_HBM_GBPS, 4)}
+    del x, codes, scales
+
+    # ---- 3. back-to-back bf16 MFMAs (one wave per SIMD, nothing else in the loop) on operands of different bit activity
+    slices, iters, wgs = 1024, 4096, 256
+    operands = {
+        "zeros": (np.zeros((slices, 512), dtype=np.uint16), np.zeros((slices, 512), dtype=np.uint16)),
+        "ones": (np.full((slices, 512), 0x3f80, dtype=np.uint16), np.full((slices, 512), 0x3f80, dtype=np.uint16)),
+        "normal": (normal_bf16(rng, (slices, 512)), normal_bf16(rng, (slices, 512))),
+    }
+    res = torch.zeros(wgs * 8, dtype=torch.float32, device="cuda")
+    flops = wgs * 4 * iters * 16 * 32768
+    out["mfma_bf16_32x32x16"] = {}
+    for name, (ah, bh) in operands.items():
+        a, b = dev_bf16(ah), dev_bf16(bh)
+        med, _, mn = median_ms(torch, lambda: probes.slim_probe_mfma_bf16(a, b, res, wgs, iters), 40, warm=20)
+        cyc = float(res.view(-1, 2)[:, 1].mean())
+        out["mfma_bf16_32x32x16"][name] = {
+            "ms_median": round(med, 4), "TFLOPs": round(flops / med / 1e9, 1), "frac_of_bf16_mfma_peak": round(flops / med / 1e9 / PEAK_BF16_TFLOPS, 4),
+            "cycles_per_wave_loop": round(cyc), "cycles_per_mfma": round(cyc / (iters * 16), 2),
+            "effective_clock_GHz": round(cyc / (med * 1e6), 3)}
+
+    # ---- 4. the prefill kernel itself on the same three kinds of operands
+    out["prefill"] = {}
+    for label, (B, H, S, causal) in (("C2 causal", (1, 32, 2048, True)), ("S=8192 non-causal", (1, 32, 8192, False))):
+        fl = acct.prefill_flops(B, H, S, 128, causal)
+        rec = {}
+        for name in ("zeros", "ones", "normal"):
+            shape = (B, H, S, 128)
+            if name == "normal":
+                q, k, v = (dev_bf16(normal_bf16(rng, shape)) for _ in range(3))
+            else:
+                fill = 0.0 if name == "zeros" else 1.0
+                q, k, v = (torch.full(shape, fill, dtype=torch.bfloat16, device="cuda") for _ in range(3))
+            o = torch.empty_like(q)
+            scale = 1.0 / float(np.sqrt(128.0))
+            med, _, mn = median_ms(torch, lambda: sa.slim_attn_prefill(q, k, v, scale, causal, out=o), 40 if S == 2048 else 15, warm=20)
+            rec[name] = {"ms_median": round(med, 4), "ms_min": round(mn, 4), "TFLOPs": round(fl / med / 1e9, 1)}
+            del q, k, v, o
+        out["prefill"][label] = rec
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -61,27 +199,34 @@ def main():
                     help="before the warm-up steps, run untimed steps for this long: the GPU clocks take about 40 ms of "
                          "load to leave their idle state (the first ~160 steps run up to 1.5x slower)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-extras", action="store_true", help="skip the INT8 prefill workloads reported beside the headline")
+    ap.add_argument("--no-extras", action="store_true", help="skip the workloads reported beside the headline")
     ap.add_argument("--traffic-probe", action="store_true",
                     help="before the steps, run one plain 256 MiB device copy (a kernel of known HBM traffic) so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run of this command can be scaled")
     ap.add_argument("--only", choices=["all", "prefill", "decode", "quant"], default="all",
                     help="run only one kernel per step (for profiling); the JSON line then carries only its fields")
+    ap.add_argument("--probe", choices=["ceilings"], default=None,
+                    help="run the measurement kernels instead of the path and print their JSON line")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (nothing on the path needs a second); run with --gpus 1",
               file=sys.stderr)
         sys.exit(2)
+    if args.probe == "ceilings":
+        probe_ceilings(args)
+        return
 
     import torch
     from paper_2407_07304_amd import slimattn as sa
     from paper_2407_07304_amd import accounting as acct
-    from paper_2407_07304_amd.inputs import WORKLOADS, make_qkv
+    from paper_2407_07304_amd.inputs import WORKLOADS, make_qkv, make_shape
 
     sa.load()   # raises if the HIP library has not been built: there is no fallback
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     torch.cuda.set_device(0)
     dev_name = torch.cuda.get_device_name(0)
+    table3 = paper_table3_ms()
+    prof = profiled_traffic()
 
     def dev_bf16(bits):
         return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
@@ -90,6 +235,7 @@ def main():
     do_prefill = args.only in ("all", "prefill")
     do_quant = args.only in ("all", "quant")
     do_decode = args.only in ("all", "decode")
+    do_extras = args.only == "all" and not args.no_extras
 
     # ---- inputs (host-seeded, then resident in HBM)
     q2h, k2h, v2h = make_qkv(c2)
@@ -102,8 +248,11 @@ def main():
     if do_decode:
         q4h, k4h, v4h = make_qkv(c4)
         q4 = dev_bf16(q4h)
-        kc4, ks4 = sa.kv_quant_int8(dev_bf16(k4h))
+        k4 = dev_bf16(k4h)
         del k4h
+        kc4, ks4 = sa.kv_quant_int8(k4)
+        if not do_extras:
+            del k4
         vc4, vs4 = sa.kv_quant_int8(dev_bf16(v4h))
         del v4h
         o4 = torch.empty_like(q4)
@@ -166,15 +315,17 @@ def main():
     pre_flops = acct.prefill_flops(c2.batch, c2.q_heads, c2.seq_len, c2.head_dim, True)
     if do_prefill:
         tfl = pre_flops / (pre_ms * 1e-3) / 1e12
+        roof = {"kernel": "slim_prefill_kernel<128,bf16 kv,bf16 out>", "bound": "mfma", "achieved": round(tfl, 2),
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tfl / PEAK_BF16_TFLOPS, 4),
+                "target_frac": 0.5, "target_met": bool(tfl / PEAK_BF16_TFLOPS >= 0.5)}
+        roof.update(traffic_fields(prof, "prefill_c2"))
         line.update({
             "value": round(tfl, 2), "unit": "TFLOP/s",
             "prefill": {"workload": "C2", "ms": round(float(pre_ms), 4), "ms_min": round(float(pre_min), 4),
                         "ms_median": round(float(pre_med), 4), "tflops": round(tfl, 2), "frac_of_bf16_mfma_peak": round(tfl / PEAK_BF16_TFLOPS, 4),
                         "flops": pre_flops,
-                        "paper_cpu_ms_context": PAPER_TABLE3_MS[2048]},
-            "roofline": {"kernel": "slim_prefill_kernel<128,bf16 kv,bf16 out>", "bound": "mfma", "achieved": round(tfl, 2),
-                         "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(tfl / PEAK_BF16_TFLOPS, 4),
-                         "traffic": measured_traffic().get("prefill_c2")},
+                        "paper_cpu_ms_context": table3.get(c2.seq_len)},
+            "roofline": roof,
         })
     if do_decode:
         dbytes = acct.decode_bytes(c4.batch, c4.q_heads, c4.kv_heads, c4.seq_len, c4.head_dim)
@@ -182,16 +333,17 @@ def main():
         line["decode"] = {"workload": "C4", "value": round(gbps, 1), "unit": "GB/s", "ms": round(float(dec_ms), 4),
                           "ms_min": round(float(dec_min), 4), "ms_median": round(float(dec_med), 4), "bytes": dbytes,
                           "frac_of_hbm_peak": round(gbps / PEAK_HBM_GBPS, 4)}
-        line["roofline_decode"] = {"kernel": "slim_decode_int8_split_kernel<128> + slim_decode_combine_kernel<128>",
-                                   "bound": "hbm", "achieved": round(gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
-                                   "frac": round(gbps / PEAK_HBM_GBPS, 4),
-                                   "traffic": measured_traffic().get("decode_c4")}
+        roof = {"kernel": "slim_decode_int8_split_kernel<128> + slim_decode_combine_kernel<128>",
+                "bound": "hbm", "achieved": round(gbps, 1), "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                "frac": round(gbps / PEAK_HBM_GBPS, 4), "target_frac": 0.7, "target_met": bool(gbps / PEAK_HBM_GBPS >= 0.7)}
+        roof.update(traffic_fields(prof, "decode_c4"))
+        line["roofline_decode"] = roof
         if not do_prefill:
             line.update({"value": round(gbps, 1), "unit": "GB/s"})
     if do_quant:
         qbytes = 2 * acct.kv_quant_bytes(c2.batch * c2.kv_heads * c2.seq_len, c2.head_dim)
         qg = qbytes / (quant_ms * 1e-3) / 1e9
-        line["kv_quant"] = {"workload": "K and V of C2", "ms": round(float(quant_ms), 4),
+        line["kv_quant"] = {"workload": "K and V of C2 (two launches)", "ms": round(float(quant_ms), 4),
                             "ms_median": round(float(quant_med), 4), "GBps": round(qg, 1),
                             "bytes": qbytes, "frac_of_hbm_peak": round(qg / PEAK_HBM_GBPS, 4)}
         if not (do_prefill or do_decode):
@@ -203,133 +355,135 @@ def main():
         "settle_ms": args.settle_ms,   # untimed steps before the warm-up steps, until the clocks have left idle
     }
 
-    # ---- INT8-KV prefill workloads beside the headline (device-seeded N(0,1); a few launches each)
-    if args.only == "all" and not args.no_extras:
+    # ---- the other workloads, beside the headline.  Inputs from the same host generator; K/V quantised by the
+    # library's quantiser (the parity tests hold it bit for bit to the oracle's on these very tensors).
+    kept = {}   # what the CPU leg below compares: host inputs and sampled GPU output rows of C3 and C5
+    if do_extras:
         extras = []
-        for name, iters in (("C3", 10), ("C5", 3)):
+        for name, iters in (("C3", 30), ("C5", 20)):
             w = WORKLOADS[name]
-            g = torch.Generator(device="cuda")
-            g.manual_seed(w.seed)
-            qx = torch.randn((w.batch, w.q_heads, w.seq_len, w.head_dim), generator=g, device="cuda",
-                             dtype=torch.float32).to(torch.bfloat16)
-            kx = torch.randn((w.batch, w.kv_heads, w.seq_len, w.head_dim), generator=g, device="cuda",
-                             dtype=torch.float32).to(torch.bfloat16)
-            vx = torch.randn((w.batch, w.kv_heads, w.seq_len, w.head_dim), generator=g, device="cuda",
-                             dtype=torch.float32).to(torch.bfloat16)
-            kcx, ksx = sa.kv_quant_int8(kx)
-            vcx, vsx = sa.kv_quant_int8(vx)
+            qh, kh, vh = make_qkv(w)
+            qx = dev_bf16(qh)
+            kcx, ksx = sa.kv_quant_int8(dev_bf16(kh))
+            vcx, vsx = sa.kv_quant_int8(dev_bf16(vh))
             ox = torch.empty_like(qx)
-            for _ in range(2):
-                sa.slim_attn_prefill(qx, kcx, vcx, w.softmax_scale, True, k_scale=ksx, v_scale=vsx, out=ox)
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(iters):
-                sa.slim_attn_prefill(qx, kcx, vcx, w.softmax_scale, True, k_scale=ksx, v_scale=vsx, out=ox)
-            e1.record()
-            torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / iters
+            med, mean, mn = median_ms(torch, lambda: sa.slim_attn_prefill(qx, kcx, vcx, w.softmax_scale, True, k_scale=ksx,
+                                                                           v_scale=vsx, out=ox), iters)
             fl = acct.prefill_flops(w.batch, w.q_heads, w.seq_len, w.head_dim, True)
-            tf = fl / (ms * 1e-3) / 1e12
-            rec = {"workload": name + " causal prefill, INT8 K/V", "ms": round(ms, 4), "tflops": round(tf, 2),
-                   "frac_of_bf16_mfma_peak": round(tf / PEAK_BF16_TFLOPS, 4),
-                   "paper_cpu_ms_context": PAPER_TABLE3_MS.get(w.seq_len)}
+            tf = fl / (mean * 1e-3) / 1e12
+            rec = {"workload": name + " causal prefill, INT8 K/V", "launches": iters, "ms": round(mean, 4), "ms_median": round(med, 4),
+                   "ms_min": round(mn, 4), "tflops": round(tf, 2), "frac_of_bf16_mfma_peak": round(tf / PEAK_BF16_TFLOPS, 4),
+                   "paper_cpu_ms_context": table3.get(w.seq_len)}
+            rows = _sample_rows(w.seq_len, 57 if name == "C3" else 9, w.seed)
+            kept[name] = (w, qh, kh, vh, rows, ox[:, :, torch.from_numpy(rows).long().cuda()].double().cpu().numpy(),
+                          kcx.cpu().numpy(), ksx.cpu().numpy(), vcx.cpu().numpy(), vsx.cpu().numpy())
             if name == "C3":
                 # information only: what the INT8 cache costs in accuracy (the paper gives no bound): the same
                 # attention on the unquantised bf16 K/V, both from this library's kernels
-                ob = sa.slim_attn_prefill(qx, kx, vx, w.softmax_scale, True)
+                ob = sa.slim_attn_prefill(qx, dev_bf16(kh), dev_bf16(vh), w.softmax_scale, True)
                 torch.cuda.synchronize()
                 diff = (ox.float() - ob.float()).abs()
                 rec["int8_kv_vs_bf16_kv_output"] = {"max_abs": round(float(diff.max()), 5),
                                                     "mean_abs": round(float(diff.mean()), 6)}
                 del ob, diff
             extras.append(rec)
-            del qx, kx, vx, kcx, vcx, ksx, vsx, ox
+            del qx, kcx, vcx, ksx, vsx, ox
+
         # ---- C2 prefill that also writes the INT8 cache, against the step's own prefill + two quantiser launches
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(50)]
-        for i in range(60):
-            step()
-            if i >= 10:
-                evs[i - 10][0].record()
-            sa.slim_attn_prefill_emit_int8(q2, k2, v2, c2.softmax_scale, True, out=o2)
-            if i >= 10:
-                evs[i - 10][1].record()
-        torch.cuda.synchronize()
-        te = np.array([a.elapsed_time(b) for a, b in evs])
+        med, mean, _ = median_ms(torch, lambda: sa.slim_attn_prefill_emit_int8(q2, k2, v2, c2.softmax_scale, True, out=o2),
+                                 50, warm=10, between=step)
         extras.append({"workload": "C2 causal prefill that also emits the INT8 K/V cache (one launch)",
-                       "ms": round(float(te.mean()), 4), "ms_median": round(float(np.median(te)), 4),
+                       "ms": round(mean, 4), "ms_median": round(med, 4),
                        "separate_launches_ms": round(float(pre_ms + quant_ms), 4)})
 
-        # ---- C2 in the two-sweep order (row maxima first, then the exponentials against them), beside the
-        # one-sweep kernel the step times
+        # ---- the two full-row orders of section 2.1 on C2, beside the streamed one-sweep kernel the step times
         ws2 = torch.empty((c2.batch * c2.q_heads * c2.seq_len * 2,), dtype=torch.float32, device="cuda")
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(50)]
-        for i in range(60):
-            step()
-            if i >= 10:
-                evs[i - 10][0].record()
-            sa.slim_attn_prefill_two_sweep(q2, k2, v2, c2.softmax_scale, True, out=o2, workspace=ws2)
-            if i >= 10:
-                evs[i - 10][1].record()
-        torch.cuda.synchronize()
-        tt = np.array([a.elapsed_time(b) for a, b in evs])
+        med, mean, _ = median_ms(torch, lambda: sa.slim_attn_prefill_two_sweep(q2, k2, v2, c2.softmax_scale, True, out=o2,
+                                                                                workspace=ws2), 50, warm=10, between=step)
         extras.append({"workload": "C2 causal prefill in two sweeps over K (comparison variant, two launches)",
-                       "ms": round(float(tt.mean()), 4), "ms_median": round(float(np.median(tt)), 4),
-                       "one_sweep_ms": round(float(pre_ms), 4)})
+                       "ms": round(mean, 4), "ms_median": round(med, 4), "one_sweep_ms": round(float(pre_ms), 4)})
         del ws2
+        if hasattr(sa, "slim_attn_prefill_strip"):
+            med, mean, _ = median_ms(torch, lambda: sa.slim_attn_prefill_strip(q2, k2, v2, c2.softmax_scale, True, out=o2),
+                                     50, warm=10, between=step)
+            fl = acct.prefill_flops(c2.batch, c2.q_heads, c2.seq_len, c2.head_dim, True)
+            extras.append({"workload": "C2 causal prefill with the whole score strip of a row block on chip (comparison "
+                                       "variant, one launch)", "ms": round(mean, 4), "ms_median": round(med, 4),
+                           "tflops": round(fl / (mean * 1e-3) / 1e12, 2), "one_sweep_ms": round(float(pre_ms), 4)})
 
         # ---- decode on the grouped-query shape of the paper's larger model (64 query heads on 8 KV heads)
         Bg, Hqg, Hkvg, Tg, Dg = 16, 64, 8, 8192, 128
-        g = torch.Generator(device="cuda")
-        g.manual_seed(6)
-        qg = torch.randn((Bg, Hqg, 1, Dg), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
-        caches = []
-        for _ in range(2):
-            x = torch.randn((Bg, Hkvg, Tg, Dg), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
-            caches.append(sa.kv_quant_int8(x))
-            del x
-        (kcg, ksg), (vcg, vsg) = caches
-        og = torch.empty_like(qg)
+        wg = make_shape("decode", Bg, Hqg, Hkvg, Tg, Dg, False, True, False, 6, name="GQA decode")
+        qgh, kgh, vgh = make_qkv(wg)
+        qg_ = dev_bf16(qgh)
+        kcg, ksg = sa.kv_quant_int8(dev_bf16(kgh))
+        vcg, vsg = sa.kv_quant_int8(dev_bf16(vgh))
+        del kgh, vgh
+        og = torch.empty_like(qg_)
         wsg = torch.empty((sa.slim_attn_decode_int8_workspace_bytes(Bg, Hqg, Hkvg, Tg, Dg),), dtype=torch.uint8, device="cuda")
-        sg = 1.0 / float(np.sqrt(Dg))
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(50)]
-        for i in range(60):
-            step()   # the C4 decode of a step streams 1.1 GB: this cache (277 MB) is out of the caches again
-            if i >= 10:
-                evs[i - 10][0].record()
-            sa.slim_attn_decode_int8(qg, kcg, ksg, vcg, vsg, sg, out=og, workspace=wsg)
-            if i >= 10:
-                evs[i - 10][1].record()
-        torch.cuda.synchronize()
-        tg = np.array([a.elapsed_time(b) for a, b in evs])
+        # (the C4 decode of a step streams 1.1 GB: this cache, 277 MB, is out of the caches again before every launch)
+        med, mean, _ = median_ms(torch, lambda: sa.slim_attn_decode_int8(qg_, kcg, ksg, vcg, vsg, wg.softmax_scale, out=og,
+                                                                          workspace=wsg), 50, warm=10, between=step)
         gbytes = acct.decode_bytes(Bg, Hqg, Hkvg, Tg, Dg)
         extras.append({"workload": "decode B=16 Hq=64 Hkv=8 T=8192 D=128 INT8 KV (grouped query heads)",
-                       "ms": round(float(tg.mean()), 4), "ms_median": round(float(np.median(tg)), 4),
-                       "GBps": round(gbytes / (tg.mean() * 1e-3) / 1e9, 1), "bytes": gbytes,
-                       "frac_of_hbm_peak": round(gbytes / (tg.mean() * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4)})
-        del qg, kcg, ksg, vcg, vsg, og, wsg
+                       "ms": round(mean, 4), "ms_median": round(med, 4),
+                       "GBps": round(gbytes / (mean * 1e-3) / 1e9, 1), "bytes": gbytes,
+                       "frac_of_hbm_peak": round(gbytes / (mean * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4)})
+        del qg_, kcg, ksg, vcg, vsg, og, wsg
+
+        # ---- the quantiser on a stream that no cache holds: K of the C4 cache (1.07 GB in, 0.54 GB out)
+        if do_decode:
+            med, mean, _ = median_ms(torch, lambda: sa.kv_quant_int8(k4, kc4, ks4), 20)   # (the same codes again)
+            sbytes = acct.kv_quant_bytes(c4.batch * c4.kv_heads * c4.seq_len, c4.head_dim)
+            extras.append({"workload": "kv_quant_int8 on K of C4 (B=16, 32 heads, 8192 tokens: 1.07 GB bf16 in, 0.55 GB out)",
+                           "ms": round(mean, 4), "ms_median": round(med, 4), "GBps": round(sbytes / (mean * 1e-3) / 1e9, 1),
+                           "bytes": sbytes, "frac_of_hbm_peak": round(sbytes / (mean * 1e-3) / 1e9 / PEAK_HBM_GBPS, 4)})
+            del k4
         line["other_workloads"] = extras
 
-    # ---- the CPU oracle on this host's cores, beside the GPU number (a baseline, not a target)
+    # ---- the CPU oracle on this host's cores, beside the GPU numbers (a baseline, not a target), and the GPU
+    # outputs held against it
     if not args.no_cpu_baseline and do_prefill:
         import oracle
-        n_heads = c2.q_heads                          # the whole C2 tensor: under a second of CPU work on the box
+        sa.slim_attn_prefill(q2, k2, v2, c2.softmax_scale, True, out=o2)
+        torch.cuda.synchronize()
         t0 = time.perf_counter()
-        oracle.attn(q2h[:, :n_heads], k2h[:, :n_heads], v2h[:, :n_heads], c2.softmax_scale, True)
+        want = oracle.attn(q2h, k2h, v2h, c2.softmax_scale, True)   # the whole C2 tensor: under a second on the box
         dt = time.perf_counter() - t0
-        fl = acct.prefill_flops(c2.batch, n_heads, c2.seq_len, c2.head_dim, True)
+        err = np.abs(o2.double().cpu().numpy() - want)
+        fl = acct.prefill_flops(c2.batch, c2.q_heads, c2.seq_len, c2.head_dim, True)
         line["cpu_baseline"] = {"value": round(fl / dt / 1e12, 5), "unit": "TFLOP/s", "cores": oracle.num_threads(),
                                 "cpu_model": _cpu_model(), "kind": "oracle", "seconds": round(dt, 3),
-                                "sample": "the whole C2 tensor: 32 heads, 2048 rows (fp64 scalar C, OpenMP)"}
+                                "sample": "the whole C2 tensor: 32 heads, 2048 rows (fp64 scalar C, OpenMP)",
+                                "gpu_vs_oracle": {"max_abs": float("%.3e" % err.max()), "mean_abs": float("%.3e" % err.mean())}}
+        del want, err
         if do_decode:
-            nb = c4.batch
-            kc, ks, vc, vs = (t[:nb].cpu().numpy() for t in (kc4, ks4, vc4, vs4))
+            kc, ks, vc, vs = (t.cpu().numpy() for t in (kc4, ks4, vc4, vs4))
             t0 = time.perf_counter()
-            oracle.attn(q4h[:nb], kc, vc, c4.softmax_scale, False, k_scale=ks, v_scale=vs)
+            want = oracle.attn(q4h, kc, vc, c4.softmax_scale, False, k_scale=ks, v_scale=vs)
             dt = time.perf_counter() - t0
-            by = acct.decode_bytes(nb, c4.q_heads, c4.kv_heads, c4.seq_len, c4.head_dim)
+            err = np.abs(o4.double().cpu().numpy() - want)
+            by = acct.decode_bytes(c4.batch, c4.q_heads, c4.kv_heads, c4.seq_len, c4.head_dim)
             line["cpu_baseline_decode"] = {"value": round(by / dt / 1e9, 3), "unit": "GB/s",
                                            "cores": oracle.num_threads(), "kind": "oracle", "seconds": round(dt, 3),
-                                           "sample": "the whole C4 step: 16 sequences, 32 heads, 8192 tokens"}
+                                           "sample": "the whole C4 step: 16 sequences, 32 heads, 8192 tokens",
+                                           "gpu_vs_oracle": {"max_abs": float("%.3e" % err.max()), "mean_abs": float("%.3e" % err.mean())}}
+            del kc, ks, vc, vs, want
+        others = []
+        for name, (w, qh, kh, vh, rows, got, gkc, gks, gvc, gvs) in kept.items():
+            okc, oks = oracle.kv_quant_int8(kh)
+            ovc, ovs = oracle.kv_quant_int8(vh)
+            exact = bool(np.array_equal(okc, gkc) and np.array_equal(ovc, gvc) and
+                         np.array_equal(oks.view(np.uint32), gks.view(np.uint32)) and np.array_equal(ovs.view(np.uint32), gvs.view(np.uint32)))
+            t0 = time.perf_counter()
+            want = oracle.attn(qh, okc, ovc, w.softmax_scale, True, k_scale=oks, v_scale=ovs, rows=rows)
+            dt = time.perf_counter() - t0
+            err = np.abs(got - want)
+            others.append({"workload": name, "kind": "oracle", "sample": "%d query rows of every head" % rows.size,
+                           "seconds": round(dt, 3), "int8_cache_bit_exact": exact,
+                           "gpu_vs_oracle": {"max_abs": float("%.3e" % err.max()), "mean_abs": float("%.3e" % err.mean())}})
+        if others:
+            line["cpu_baseline_other_workloads"] = others
     print(json.dumps(line))
 
 

@@ -12,7 +12,8 @@
  * and, around them, what a serving loop needs: kv_quant_int8_append (one new token per
  * sequence into the cache), slim_attn_prefill_emit_int8 (prefill that also writes the
  * cache), slim_attn_decode_int8_varlen (a batch whose caches differ in length), plus
- * slim_attn_prefill_two_sweep, a comparison variant of the prefill.
+ * slim_attn_prefill_two_sweep and slim_attn_prefill_strip, two comparison variants of the prefill that keep the
+ * paper's own order of operations (the whole score row before the softmax).
  *
  * Common rules
  *   - Every pointer marked "device" is GPU memory owned by the caller, 16-byte
@@ -141,6 +142,25 @@ int slim_attn_prefill_two_sweep(const void* q_bf16, const void* k_bf16, const vo
                                 void* workspace, size_t workspace_bytes,
                                 int batch, int q_heads, int kv_heads, int seq_len, int head_dim,
                                 int causal, float softmax_scale, int out_dtype, void* stream);
+
+/*
+ * Second comparison variant of the bf16 prefill, the order of operations of section 2.1 with nothing computed
+ * twice: the whole score strip of a row block (its query rows times ALL their keys) is kept on chip, the softmax
+ * is applied to it once (one maximum, one pass of exponentials, one sum; no running maximum, no rescaling), and
+ * the strip times V is the row block's slice of the output; the next row block reuses the buffer.  The buffer is
+ * the compute unit's local memory (160 KB), which holds 32 query rows x slim_attn_prefill_strip_max_seq_len()
+ * (2048) keys of fp16 scores: that fixes the row block at 32 rows, so K and V are read four times as often as by
+ * the 128-row blocks of slim_attn_prefill.  A score waits in the strip as fp16 relative to the row maximum found
+ * so far (exact enough wherever the probability is not negligible, whatever the scores' magnitude).  A longer
+ * sequence takes the streamed kernel of slim_attn_prefill instead (same result).
+ * Same result as slim_attn_prefill up to rounding order.  K/V are bf16; everything else as in slim_attn_prefill.
+ * It is there to be measured against the streamed kernel (the question behind the paper's Table 3: one- against
+ * two-dimensional decomposition), not to be served from.
+ */
+int slim_attn_prefill_strip_max_seq_len(void);
+int slim_attn_prefill_strip(const void* q_bf16, const void* k_bf16, const void* v_bf16, void* out,
+                            int batch, int q_heads, int kv_heads, int seq_len, int head_dim,
+                            int causal, float softmax_scale, int out_dtype, void* stream);
 
 /*
  * Bytes of device workspace slim_attn_decode_int8 needs for this shape (partial

@@ -92,7 +92,8 @@ int kv_quant_int8_append(const void* x_new_bf16, int8_t* codes, float* scales, c
 static int prefill_common(const void* q_bf16, const void* k, const void* v, const float* k_scale, const float* v_scale,
                           void* out, int8_t* k_codes_out, float* k_scale_out, int8_t* v_codes_out, float* v_scale_out,
                           int batch, int q_heads, int kv_heads, int seq_len, int head_dim, int causal,
-                          float softmax_scale, int kv_dtype, int out_dtype, float* row_max, void* stream) {
+                          float softmax_scale, int kv_dtype, int out_dtype, float* row_max, void* stream,
+                          bool use_strip = false) {
     if (!q_bf16 || !k || !v || !out) return SLIM_ERR_NULL;
     if (kv_dtype != SLIM_BF16 && kv_dtype != SLIM_I8) return SLIM_ERR_UNSUPPORTED;
     if (out_dtype != SLIM_BF16 && out_dtype != SLIM_F32) return SLIM_ERR_UNSUPPORTED;
@@ -128,7 +129,7 @@ static int prefill_common(const void* q_bf16, const void* k, const void* v, cons
     a.out_f32 = out_dtype == SLIM_F32;
     a.row_max = row_max;
     drop_stale_hip_error();
-    const hipError_t e = slim::launch_prefill(a, (hipStream_t)stream);
+    const hipError_t e = use_strip ? slim::launch_prefill_strip(a, (hipStream_t)stream) : slim::launch_prefill(a, (hipStream_t)stream);
     return e == hipSuccess ? SLIM_OK : SLIM_ERR_LAUNCH;
 }
 
@@ -153,6 +154,17 @@ int slim_attn_prefill_two_sweep(const void* q_bf16, const void* k_bf16, const vo
     if (need != 0 && workspace_bytes < need) return SLIM_ERR_WORKSPACE;
     return prefill_common(q_bf16, k_bf16, v_bf16, nullptr, nullptr, out, nullptr, nullptr, nullptr, nullptr, batch, q_heads,
                           kv_heads, seq_len, head_dim, causal, softmax_scale, SLIM_BF16, out_dtype, (float*)workspace, stream);
+}
+
+int slim_attn_prefill_strip_max_seq_len(void) { return slim::kPrefillStripMaxSeqLen; }
+
+int slim_attn_prefill_strip(const void* q_bf16, const void* k_bf16, const void* v_bf16, void* out, int batch, int q_heads,
+                            int kv_heads, int seq_len, int head_dim, int causal, float softmax_scale, int out_dtype,
+                            void* stream) {
+    // a longer sequence's strip does not fit on chip: it takes the streamed kernel
+    const bool fits = seq_len <= slim::kPrefillStripMaxSeqLen;
+    return prefill_common(q_bf16, k_bf16, v_bf16, nullptr, nullptr, out, nullptr, nullptr, nullptr, nullptr, batch, q_heads,
+                          kv_heads, seq_len, head_dim, causal, softmax_scale, SLIM_BF16, out_dtype, nullptr, stream, fits);
 }
 
 int slim_attn_prefill_emit_int8(const void* q_bf16, const void* k_bf16, const void* v_bf16, void* out, int8_t* k_codes,

@@ -1,34 +1,52 @@
 // INT8 KV-cache quantiser (paper section 2.2: INT8 K/V, one scale per token per head).
 //
 // One row of D bf16 values (one token of one head) is held by D/8 adjacent lanes, 16
-// bytes each.  amax is reduced across those lanes, scale = amax / 127 and
-// code = rint(x / scale) use IEEE fp32 division (correctly rounded, denormals kept) so
-// that codes and scales are reproducible bit for bit on any IEEE machine.
+// bytes each.  amax is reduced across those lanes; scale = amax / 127 and
+// code = rint(x / scale) are defined by IEEE fp32 division (correctly rounded, denormals
+// kept), so that codes and scales are reproducible bit for bit on any IEEE machine; the row
+// routine reaches those bits by a shorter route wherever that is proved to be safe and by the
+// divisions themselves elsewhere (slim_common.h).
 // Streaming kernel: 2 B read + 1 B written per element, plus 4 B per row.
 #include "slim_common.h"
 #include "slim_kernels.h"
 
 namespace slim {
 
-// STREAM: input and output together are larger than the last-level cache, so the input is read with non-temporal loads (4.3 -> 4.6 TB/s
-// on a 1.6 GB cache, 3.8 -> 4.7 TB/s on 400 MB).  A smaller input may be what the next kernel reads again (the
-// K/V of a prefill): it is left to the caches.
-template <int D, bool STREAM>
+// STREAM: input and output together are larger than the last-level cache, so the input is read with
+// non-temporal loads and every thread keeps U = 4 rows in flight (all loads issued before any is used): 5.6 TB/s on
+// a 1.6 GB stream, where the same loads and stores with no arithmetic in between reach 5.9.  A smaller input may
+// be what the next kernel reads again (the K/V of a prefill): it is left to the caches, one row per thread, which
+// finishes a launch-bound call soonest.
+template <int D, bool STREAM, int U>
 __global__ __launch_bounds__(256) void kv_quant_int8_kernel(const uint16_t* __restrict__ x, int8_t* __restrict__ codes,
                                                             float* __restrict__ scales, long n_rows) {
     constexpr int LPR = D / 8;           // lanes per row
-    constexpr int ROWS = 256 / LPR;      // rows per workgroup pass
+    constexpr int ROWS = 256 / LPR;      // rows per workgroup and load
     const int lane_in_row = threadIdx.x % LPR;
-    const long row0 = (long)blockIdx.x * ROWS + threadIdx.x / LPR;
-    const long stride = (long)gridDim.x * ROWS;
-    for (long row = row0; row < n_rows; row += stride) {   // rows past the end leave whole row groups idle together
-        const u32x4* src = reinterpret_cast<const u32x4*>(x + row * D + lane_in_row * 8);
-        const u32x4 raw = STREAM ? __builtin_nontemporal_load(src) : *src;
-        u32x2 out2;
-        float scale;
-        quant_row_piece<LPR>(raw, out2, scale);
-        *reinterpret_cast<u32x2*>(codes + row * D + lane_in_row * 8) = out2;
-        if (lane_in_row == 0) scales[row] = scale;
+    const long stride = (long)gridDim.x * (ROWS * U);
+    // (rows past the end re-read the last row and store nothing: every lane stays in the loop as long as its
+    // wave does, so the row routine's shuffles and its wave-wide vote see whole waves)
+    const long first = (long)blockIdx.x * (ROWS * U);
+    for (long base = first; base < n_rows; base += stride) {
+        const long row0 = base + threadIdx.x / LPR;
+        u32x4 raw[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const long row = min(row0 + (long)u * ROWS, n_rows - 1);
+            const u32x4* src = reinterpret_cast<const u32x4*>(x + row * D + lane_in_row * 8);
+            raw[u] = STREAM ? __builtin_nontemporal_load(src) : *src;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const long row = row0 + (long)u * ROWS;
+            u32x2 out2;
+            float scale;
+            quant_row_piece<LPR>(raw[u], out2, scale);
+            if (row < n_rows) {
+                *reinterpret_cast<u32x2*>(codes + row * D + lane_in_row * 8) = out2;
+                if (lane_in_row == 0) scales[row] = scale;
+            }
+        }
     }
 }
 
@@ -56,18 +74,19 @@ __global__ __launch_bounds__(256) void kv_quant_int8_append_kernel(const uint16_
 
 hipError_t launch_kv_quant_int8(const void* x, int8_t* codes, float* scales, long n_rows, int head_dim,
                                 hipStream_t stream) {
-    const int rows_per_block = 256 / (head_dim / 8);
-    long blocks = (n_rows + rows_per_block - 1) / rows_per_block;
-    const long max_blocks = 256L * 64;   // 256 CUs; beyond this the grid-stride loop takes over
-    if (blocks > max_blocks) blocks = max_blocks;
     const bool stream_in = n_rows * head_dim * 3 > (256L << 20);   // input + codes beyond the 256 MB last-level cache
+    const int rows_per_block = 256 / (head_dim / 8) * (stream_in ? 4 : 1);
+    long blocks = (n_rows + rows_per_block - 1) / rows_per_block;
+    // one pass per workgroup (measured faster than fewer workgroups that loop); the loop is for grids beyond this
+    const long max_blocks = 1L << 20;
+    if (blocks > max_blocks) blocks = max_blocks;
     const dim3 grid((unsigned)blocks), block(256);
     if (head_dim == 128) {
-        if (stream_in) hipLaunchKernelGGL((kv_quant_int8_kernel<128, true>), grid, block, 0, stream, (const uint16_t*)x, codes, scales, n_rows);
-        else hipLaunchKernelGGL((kv_quant_int8_kernel<128, false>), grid, block, 0, stream, (const uint16_t*)x, codes, scales, n_rows);
+        if (stream_in) hipLaunchKernelGGL((kv_quant_int8_kernel<128, true, 4>), grid, block, 0, stream, (const uint16_t*)x, codes, scales, n_rows);
+        else hipLaunchKernelGGL((kv_quant_int8_kernel<128, false, 1>), grid, block, 0, stream, (const uint16_t*)x, codes, scales, n_rows);
     } else {
-        if (stream_in) hipLaunchKernelGGL((kv_quant_int8_kernel<64, true>), grid, block, 0, stream, (const uint16_t*)x, codes, scales, n_rows);
-        else hipLaunchKernelGGL((kv_quant_int8_kernel<64, false>), grid, block, 0, stream, (const uint16_t*)x, codes, scales, n_rows);
+        if (stream_in) hipLaunchKernelGGL((kv_quant_int8_kernel<64, true, 4>), grid, block, 0, stream, (const uint16_t*)x, codes, scales, n_rows);
+        else hipLaunchKernelGGL((kv_quant_int8_kernel<64, false, 1>), grid, block, 0, stream, (const uint16_t*)x, codes, scales, n_rows);
     }
     return hipGetLastError();
 }

@@ -29,6 +29,10 @@ struct PrefillArgs {
     float* row_max;   // null, or (bf16 K/V only) the two-sweep variant's workspace [batch, q_heads, seq_len, 2]
 };
 hipError_t launch_prefill(const PrefillArgs& a, hipStream_t stream);
+// The comparison variant that keeps a row block's whole score strip in LDS (bf16 K/V, sequences up to
+// kPrefillStripMaxSeqLen keys: 32 rows x that many fp16 scores is what fits beside the V staging buffer).
+constexpr int kPrefillStripMaxSeqLen = 2048;
+hipError_t launch_prefill_strip(const PrefillArgs& a, hipStream_t stream);
 
 struct DecodeArgs {
     const void* q;

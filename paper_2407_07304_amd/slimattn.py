@@ -45,6 +45,10 @@ def load():
         lib.slim_attn_prefill_two_sweep_workspace_bytes.restype = ctypes.c_size_t
         lib.slim_attn_prefill_two_sweep.argtypes = [p, p, p, p, p, ctypes.c_size_t, i, i, i, i, i, i, f, i, p]
         lib.slim_attn_prefill_two_sweep.restype = i
+        lib.slim_attn_prefill_strip_max_seq_len.argtypes = []
+        lib.slim_attn_prefill_strip_max_seq_len.restype = i
+        lib.slim_attn_prefill_strip.argtypes = [p, p, p, p, i, i, i, i, i, i, f, i, p]
+        lib.slim_attn_prefill_strip.restype = i
         lib.slim_attn_decode_int8_workspace_bytes.argtypes = [i, i, i, i, i]
         lib.slim_attn_decode_int8_workspace_bytes.restype = ctypes.c_size_t
         lib.slim_attn_decode_int8.argtypes = [p, p, p, p, p, p, p, ctypes.c_size_t, i, i, i, i, i, i, f, p]
@@ -226,4 +230,21 @@ def slim_attn_prefill_two_sweep(q, k, v, softmax_scale, causal=True, out=None, o
                                               _ptr(out), _ptr(workspace), workspace.numel() * workspace.element_size(),
                                               B, Hq, Hkv, S, D, int(bool(causal)), float(softmax_scale),
                                               SLIM_F32 if out.dtype == torch.float32 else SLIM_BF16, _stream()))
+    return out
+
+
+def slim_attn_prefill_strip_max_seq_len() -> int:
+    return int(load().slim_attn_prefill_strip_max_seq_len())
+
+
+def slim_attn_prefill_strip(q, k, v, softmax_scale, causal=True, out=None, out_dtype=torch.bfloat16):
+    """The comparison variant of the bf16 prefill that keeps a row block's whole score strip on chip."""
+    B, Hq, S, D = q.shape
+    Hkv = k.shape[1]
+    assert k.shape == (B, Hkv, S, D) and v.shape == k.shape and k.dtype == torch.bfloat16 and v.dtype == torch.bfloat16
+    if out is None:
+        out = torch.empty((B, Hq, S, D), dtype=out_dtype, device=q.device)
+    _check(load().slim_attn_prefill_strip(_ptr(q, torch.bfloat16), _ptr(k, torch.bfloat16), _ptr(v, torch.bfloat16), _ptr(out),
+                                          B, Hq, Hkv, S, D, int(bool(causal)), float(softmax_scale),
+                                          SLIM_F32 if out.dtype == torch.float32 else SLIM_BF16, _stream()))
     return out

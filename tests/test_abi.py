@@ -28,7 +28,8 @@ def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert {"kv_quant_int8", "slim_attn_prefill", "slim_attn_decode_int8", "slim_attn_decode_int8_varlen",
             "kv_quant_int8_append", "slim_attn_prefill_emit_int8", "slim_attn_decode_int8_workspace_bytes", "slim_status_string",
-            "slim_attn_prefill_two_sweep", "slim_attn_prefill_two_sweep_workspace_bytes"} <= set(names)
+            "slim_attn_prefill_two_sweep", "slim_attn_prefill_two_sweep_workspace_bytes", "slim_attn_prefill_strip",
+            "slim_attn_prefill_strip_max_seq_len", "slim_attn_decode_int8_static", "slim_attn_decode_int8_static_max_bytes"} <= set(names)
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -141,6 +142,34 @@ def test_prefill_two_sweep_rejects_bad_arguments(lib):
     assert call(D=96) == 3 and call(od=7) == 3
     assert call(ws=A + 4) == 4
     assert call(wb=need - 1) == 5
+
+
+def test_prefill_strip_rejects_bad_arguments(lib):
+    f = lib.slim_attn_prefill_strip
+    assert lib.slim_attn_prefill_strip_max_seq_len() == 2048
+
+    def call(q=A, k=A, v=A, out=A, S=100, D=128, od=0, Hq=4, Hkv=2, causal=1, scale=0.1):
+        return f(P(q), P(k), P(v), P(out), 1, Hq, Hkv, S, D, causal, scale, od, None)
+
+    assert call(q=None) == 1 and call(out=None) == 1
+    assert call(S=0) == 2 and call(Hq=3) == 2 and call(causal=3) == 2 and call(scale=-1.0) == 2
+    assert call(D=96) == 3 and call(od=7) == 3
+    assert call(v=A + 4) == 4
+
+
+def test_probe_library_exports_what_its_header_declares():
+    from paper_2407_07304_amd import probes
+    text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "slimprobe.h")).read(), flags=re.S)
+    names = sorted(set(re.findall(r"\b(slim_probe_[a-z_0-9]+)\s*\(", text)))
+    assert names == ["slim_probe_mfma_bf16", "slim_probe_quant_traffic", "slim_probe_stream_read"]
+    lib = probes.load()
+    for n in names:
+        assert getattr(lib, n) is not None
+    # bad arguments are refused before anything is enqueued (no GPU is touched)
+    assert lib.slim_probe_stream_read(P(None), 1024, P(A), None) == 1
+    assert lib.slim_probe_stream_read(P(A), 1000, P(A), None) == 1
+    assert lib.slim_probe_quant_traffic(P(A), P(A), P(A), 10, 96, None) == 1
+    assert lib.slim_probe_mfma_bf16(P(A), P(A), 0, P(A), 1, 1, None) == 1
 
 
 def test_prefill_emit_rejects_bad_arguments(lib):

@@ -82,7 +82,7 @@ def test_kv_quant_bit_exact_beyond_the_last_level_cache(sa, oracle, D):
 
 # ---------------------------------------------------------------- prefill
 
-def _prefill_case(sa, oracle, B, Hq, Hkv, S, D, causal, kv_int8, out_f32, seed, rows=None, two_sweep=False):
+def _prefill_case(sa, oracle, B, Hq, Hkv, S, D, causal, kv_int8, out_f32, seed, rows=None, two_sweep=False, strip=False):
     rng = np.random.default_rng(seed)
     q = normal_bf16(rng, (B, Hq, S, D))
     k = normal_bf16(rng, (B, Hkv, S, D))
@@ -97,7 +97,7 @@ def _prefill_case(sa, oracle, B, Hq, Hkv, S, D, causal, kv_int8, out_f32, seed, 
         torch.cuda.synchronize()
         want = oracle.attn(q, kc, vc, scale, causal, k_scale=ks, v_scale=vs, rows=rows)
     else:
-        fn = sa.slim_attn_prefill_two_sweep if two_sweep else sa.slim_attn_prefill
+        fn = sa.slim_attn_prefill_two_sweep if two_sweep else (sa.slim_attn_prefill_strip if strip else sa.slim_attn_prefill)
         out = fn(dev_bf16(q), dev_bf16(k), dev_bf16(v), scale, causal, out_dtype=od)
         torch.cuda.synchronize()
         want = oracle.attn(q, k, v, scale, causal, rows=rows)
@@ -667,6 +667,47 @@ def test_prefill_two_sweep_large_scores_and_repeats(sa, oracle):
     assert torch.equal(a, b)
     check_close(host_f64(a), oracle.attn(q, k, v, 2.0, True), "two-sweep, scale 2")
     assert (a - one).abs().max().item() <= 2e-2
+
+
+# ---------------------------------------------------------------- the on-chip score strip comparison variant
+
+@pytest.mark.parametrize("B,Hq,Hkv,S,D", SMALL + [(1, 2, 1, 31, 128), (1, 1, 1, 1057, 64), (2, 2, 2, 2048, 128), (1, 2, 1, 2047, 64)])
+@pytest.mark.parametrize("causal", [True, False])
+def test_prefill_strip_small_shapes(sa, oracle, B, Hq, Hkv, S, D, causal):
+    # every strip size class (512, 1024 and 2048 columns), ragged last tiles, chunks and row blocks, both head sizes
+    print("strip prefill", B, Hq, Hkv, S, D, causal, flush=True)
+    _prefill_case(sa, oracle, B, Hq, Hkv, S, D, causal, False, out_f32=(S % 2 == 1), seed=40 + S, strip=True)
+
+
+@pytest.mark.timeout(600)
+def test_prefill_strip_c2_full_size(sa, oracle):
+    w = WORKLOADS["C2"]
+    print("strip prefill C2, every row of every head", flush=True)
+    _prefill_case(sa, oracle, w.batch, w.q_heads, w.kv_heads, w.seq_len, w.head_dim, True, False, False, w.seed, strip=True)
+
+
+def test_prefill_strip_large_scores_repeats_and_long_sequences(sa, oracle):
+    # scores far from zero (the strip holds them as fp16: scale 2 on N(0,1) data with D = 128 reaches |u| of a few
+    # hundred in log2 units), the same bits on a second run, and a sequence whose strip does not fit on chip,
+    # which takes the streamed kernel and must give its bits
+    B, Hq, Hkv, S, D = 1, 4, 2, 700, 128
+    rng = np.random.default_rng(79)
+    q, k, v = normal_bf16(rng, (B, Hq, S, D)), normal_bf16(rng, (B, Hkv, S, D)), normal_bf16(rng, (B, Hkv, S, D))
+    dq, dk, dv = dev_bf16(q), dev_bf16(k), dev_bf16(v)
+    a = sa.slim_attn_prefill_strip(dq, dk, dv, 2.0, True, out_dtype=torch.float32)
+    b = sa.slim_attn_prefill_strip(dq, dk, dv, 2.0, True, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert torch.equal(a, b)
+    check_close(host_f64(a), oracle.attn(q, k, v, 2.0, True), "strip, scale 2")
+    S2 = sa.slim_attn_prefill_strip_max_seq_len() + 1
+    assert S2 == 2049
+    q, k, v = normal_bf16(rng, (1, 2, S2, 64)), normal_bf16(rng, (1, 1, S2, 64)), normal_bf16(rng, (1, 1, S2, 64))
+    dq, dk, dv = dev_bf16(q), dev_bf16(k), dev_bf16(v)
+    long_strip = sa.slim_attn_prefill_strip(dq, dk, dv, 0.125, True)
+    long_plain = sa.slim_attn_prefill(dq, dk, dv, 0.125, True)
+    torch.cuda.synchronize()
+    assert torch.equal(long_strip, long_plain)
+    check_close(host_f64(long_strip), oracle.attn(q, k, v, 0.125, True), "strip entry point beyond its length")
 
 
 # ---------------------------------------------------------------- sharp softmax: the arithmetic's own bound
