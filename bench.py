@@ -190,6 +190,39 @@ def probe_ceilings(args):
     print(json.dumps(out))
 
 
+def only_gqa_decode(args):
+    """The grouped-query decode alone (for profiling): `steps` launches, each after a 1 GiB streaming read."""
+    import torch
+    from paper_2407_07304_amd import probes, slimattn as sa
+    from paper_2407_07304_amd import accounting as acct
+    from paper_2407_07304_amd.inputs import make_qkv, make_shape
+    sa.load()
+    probes.load()
+    torch.cuda.set_device(0)
+
+    def dev_bf16(bits):
+        return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+    B, Hq, Hkv, T, D = 16, 64, 8, 8192, 128
+    w = make_shape("decode", B, Hq, Hkv, T, D, False, True, False, 6, name="GQA decode")
+    qh, kh, vh = make_qkv(w)
+    q = dev_bf16(qh)
+    kc, ks = sa.kv_quant_int8(dev_bf16(kh))
+    vc, vs = sa.kv_quant_int8(dev_bf16(vh))
+    out = torch.empty_like(q)
+    ws = torch.empty((sa.slim_attn_decode_int8_workspace_bytes(B, Hq, Hkv, T, D),), dtype=torch.uint8, device="cuda")
+    flush = torch.randint(0, 255, (1 << 30,), dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    med, mean, mn = median_ms(torch, lambda: sa.slim_attn_decode_int8(q, kc, ks, vc, vs, w.softmax_scale, out=out, workspace=ws),
+                              args.steps, warm=args.warmup, between=lambda: probes.slim_probe_stream_read(flush, sink))
+    by = acct.decode_bytes(B, Hq, Hkv, T, D)
+    print(json.dumps({"metric": "INT8-KV decode HBM GB/s, grouped query heads", "value": round(by / mean / 1e6, 1), "unit": "GB/s",
+                      "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(mean, 4), "ms_median": round(med, 4),
+                      "ms_min": round(mn, 4), "higher_is_better": True, "dtype": "bf16", "data": "synthetic", "bytes": by,
+                      "frac_of_hbm_peak": round(by / mean / 1e6 / PEAK_HBM_GBPS, 4),
+                      "config": {"workload": "decode B=16 Hq=64 Hkv=8 T=8192 D=128 INT8 KV", "only": "gqa-decode"}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -203,8 +236,10 @@ def main():
     ap.add_argument("--traffic-probe", action="store_true",
                     help="before the steps, run one plain 256 MiB device copy (a kernel of known HBM traffic) so that a "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE run of this command can be scaled")
-    ap.add_argument("--only", choices=["all", "prefill", "decode", "quant"], default="all",
-                    help="run only one kernel per step (for profiling); the JSON line then carries only its fields")
+    ap.add_argument("--only", choices=["all", "prefill", "decode", "quant", "gqa-decode"], default="all",
+                    help="run only one kernel per step (for profiling); the JSON line then carries only its fields.  "
+                         "gqa-decode: the grouped-query decode of the other workloads (B=16, 64 query heads on 8 KV heads, "
+                         "T=8192), a 1 GiB streaming read before every launch so that the cache comes from HBM")
     ap.add_argument("--probe", choices=["ceilings"], default=None,
                     help="run the measurement kernels instead of the path and print their JSON line")
     args = ap.parse_args()
@@ -214,6 +249,9 @@ def main():
         sys.exit(2)
     if args.probe == "ceilings":
         probe_ceilings(args)
+        return
+    if args.only == "gqa-decode":
+        only_gqa_decode(args)
         return
 
     import torch
