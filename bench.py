@@ -216,10 +216,16 @@ def only_gqa_decode(args):
     med, mean, mn = median_ms(torch, lambda: sa.slim_attn_decode_int8(q, kc, ks, vc, vs, w.softmax_scale, out=out, workspace=ws),
                               args.steps, warm=args.warmup, between=lambda: probes.slim_probe_stream_read(flush, sink))
     by = acct.decode_bytes(B, Hq, Hkv, T, D)
+    # the same loads without the arithmetic (and without the combine launch): what the memory system charges for this
+    # access pattern on this shape
+    tmed, tmean, tmn = median_ms(torch, lambda: probes.slim_probe_gqa_decode_traffic(q, kc, ks, vc, vs, ws), args.steps, warm=args.warmup,
+                                 between=lambda: probes.slim_probe_stream_read(flush, sink))
     print(json.dumps({"metric": "INT8-KV decode HBM GB/s, grouped query heads", "value": round(by / mean / 1e6, 1), "unit": "GB/s",
                       "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(mean, 4), "ms_median": round(med, 4),
                       "ms_min": round(mn, 4), "higher_is_better": True, "dtype": "bf16", "data": "synthetic", "bytes": by,
                       "frac_of_hbm_peak": round(by / mean / 1e6 / PEAK_HBM_GBPS, 4),
+                      "loads_only": {"ms": round(tmean, 4), "ms_median": round(tmed, 4), "ms_min": round(tmn, 4),
+                                     "GBps": round(by / tmean / 1e6, 1), "frac_of_hbm_peak": round(by / tmean / 1e6 / PEAK_HBM_GBPS, 4)},
                       "config": {"workload": "decode B=16 Hq=64 Hkv=8 T=8192 D=128 INT8 KV", "only": "gqa-decode"}}))
 
 

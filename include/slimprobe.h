@@ -1,5 +1,5 @@
 /*
- * slimprobe.h — C ABI of three measurement kernels for AMD MI355X (gfx950).
+ * slimprobe.h — C ABI of four measurement kernels for AMD MI355X (gfx950).
  *
  * They are not part of the attention path.  They exist so that the ceilings the path's kernels are judged
  * against on a given machine (what a plain streaming read reaches of the HBM peak, what the quantiser's
@@ -47,6 +47,17 @@ int slim_probe_quant_traffic(const void* x_bf16, int8_t* codes, float* scales, l
  *           and the shader-clock cycles its loop took (as a float)
  */
 int slim_probe_mfma_bf16(const void* a, const void* b, int slices, float* out, int workgroups, int iters, void* stream);
+
+/*
+ * The loads of the grouped-query decode kernel (slim_attn_decode_int8 with 2 to 32 query heads per KV head)
+ * without its arithmetic: the same workgroups, waves, token runs and 128-bit non-temporal loads of K codes, V codes
+ * and scales, issued at the same points of the same loop, a tile's registers only XORed together before they are
+ * refilled.  Arguments as for slim_attn_decode_int8 (no output: what lands in the workspace is meaningless);
+ * workspace_bytes as slim_attn_decode_int8_workspace_bytes() gives for the shape.
+ */
+int slim_probe_gqa_decode_traffic(const void* q_bf16, const int8_t* k_codes, const float* k_scale, const int8_t* v_codes,
+                                  const float* v_scale, void* workspace, size_t workspace_bytes, int batch, int q_heads,
+                                  int kv_heads, int kv_len, int head_dim, void* stream);
 
 #ifdef __cplusplus
 }

@@ -8,7 +8,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libslimattn.so")
 SOURCES = ["api.hip", "kv_quant.hip", "decode.hip", "decode_gqa.hip", "prefill.hip", "prefill_strip.hip"]
 PROBE_LIB = os.path.join(HERE, "libslimprobe.so")
-PROBE_SOURCES = ["probes.hip"]
+PROBE_SOURCES = ["probes.hip", "decode_gqa.hip"]   # (the grouped-query decode kernel has a traffic-only form)
 # prefill.hip: MFMA results stay in arch VGPRs (no AGPR copies around the softmax), and fmaxf needs no
 # NaN quieting (NaN inputs are documented as undefined).  The quantiser keeps the IEEE defaults.
 # -Wno-inline-asm: its buffer loads with an LDS destination set M0 themselves and say so in the clobber list.

@@ -27,7 +27,8 @@
 
 namespace slim {
 
-constexpr int kGqaWaves = 4;    // waves per workgroup, each with a token run of its own
+constexpr int kGqaWaves = 2;    // waves per workgroup, each with a token run of its own (the waves share nothing: on B=16, 64/8 heads,
+                                // T=8192 two-wave workgroups run 8 % faster than four-wave ones with the same runs, one-wave ones the same)
 constexpr int kGqaTile = 32;    // tokens per tile
 
 // 16 INT8 codes -> 16 bf16, exact: the first and the second eight
@@ -41,7 +42,10 @@ __device__ __forceinline__ void widen16(const u32x4 cw, u32x4& lo, u32x4& hi) {
     }
 }
 
-template <int D>
+// TRAFFIC_ONLY: the measurement form of the kernel (include/slimprobe.h): the same workgroups, waves, token runs and
+// loads, issued at the same points, but a tile's registers are only XORed together before they are refilled.  What it
+// takes is what the memory system charges for this access pattern on this shape, arithmetic aside.
+template <int D, bool TRAFFIC_ONLY = false>
 __global__ __launch_bounds__(64 * kGqaWaves) void slim_decode_int8_gqa_kernel(
     const uint16_t* __restrict__ q, const int8_t* __restrict__ kc, const float* __restrict__ ks,
     const int8_t* __restrict__ vc, const float* __restrict__ vs, float* __restrict__ ws_acc,
@@ -152,6 +156,17 @@ __global__ __launch_bounds__(64 * kGqaWaves) void slim_decode_int8_gqa_kernel(
         constexpr int P = decltype(par)::value;
         const int t0 = t_begin + i * kGqaTile;
         const bool more = i + 2 < n_tiles;
+        if constexpr (TRAFFIC_ONLY) {
+            u32x4 x = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int n = 0; n < NP; ++n) x ^= kbuf[P][n] ^ vbuf[P][n];
+            lsum += __uint_as_float((x[0] ^ x[1] ^ x[2] ^ x[3]) & 0x3fffffffu) + sc[P];
+            if (more) {
+                issue_k(par, t0 + 2 * kGqaTile);
+                issue_v(par, t0 + 2 * kGqaTile);
+            }
+            return;
+        }
 
         stage(par, kbuf, kS, ROWLK);
         scS[lane] = hh == 0 ? sc[P] * scale_log2e : sc[P];
@@ -253,16 +268,17 @@ __global__ __launch_bounds__(64 * kGqaWaves) void slim_decode_int8_gqa_kernel(
     }
 }
 
-// One wave streams tokens_per_wave tokens (a multiple of the tile), a workgroup four such runs, and k
-// workgroups share one (batch, KV head).  A compute unit holds two workgroups, the chip 512: k is chosen so
-// that (rounds of 512 workgroups) x (tiles per wave + a wave's set-up, about two tiles' worth) is smallest,
-// which avoids a last round that is nearly empty and runs that differ in length.
+// One wave streams tokens_per_wave tokens (a multiple of the tile), a workgroup kGqaWaves such runs, and k
+// workgroups share one (batch, KV head).  A compute unit holds eight waves (230 VGPRs: two per SIMD), the chip 2048:
+// k is chosen so that (rounds of resident workgroups) x (tiles per wave + a wave's set-up, about two tiles' worth) is
+// smallest, which avoids a last round that is nearly empty and runs that differ in length.
 int decode_gqa_tokens_per_wave(int kv_len, long n_bg) {
     const long tiles = ((long)kv_len + kGqaTile - 1) / kGqaTile;
     long best_k = 1, best_cost = -1;
-    for (long k = 1; k <= 16; ++k) {
+    const long resident = 2048 / kGqaWaves;   // workgroups the chip holds at a time
+    for (long k = 1; k <= 64 / kGqaWaves; ++k) {
         const long per_wave = (tiles + kGqaWaves * k - 1) / (kGqaWaves * k);
-        const long rounds = (n_bg * k + 511) / 512;
+        const long rounds = (n_bg * k + resident - 1) / resident;
         const long cost = rounds * (per_wave + 2);
         if (best_cost < 0 || cost < best_cost) {
             best_cost = cost;
@@ -280,11 +296,23 @@ int decode_gqa_num_splits(int kv_len, long n_bg) {
     return (waves + kGqaWaves - 1) / kGqaWaves * kGqaWaves;   // whole workgroups; a wave past the end writes an empty split
 }
 
-hipError_t launch_decode_gqa_split(const DecodeArgs& a, float* ws_acc, float* ws_ml, int n_split, hipStream_t stream) {
+hipError_t launch_decode_gqa_split(const DecodeArgs& a, float* ws_acc, float* ws_ml, int n_split, hipStream_t stream,
+                                   bool traffic_only) {
     const long n_bg = (long)a.batch * a.kv_heads;
     const int tpw = decode_gqa_tokens_per_wave(a.kv_len, n_bg);
     const float scale_log2e = a.softmax_scale * kLog2e;
     dim3 grid((unsigned)(n_split / kGqaWaves), (unsigned)a.kv_heads, (unsigned)a.batch);
+    if (traffic_only) {
+        if (a.head_dim == 128)
+            hipLaunchKernelGGL((slim_decode_int8_gqa_kernel<128, true>), grid, dim3(64 * kGqaWaves), 0, stream,
+                               (const uint16_t*)a.q, a.k_codes, a.k_scale, a.v_codes, a.v_scale, ws_acc, ws_ml, a.kv_lens,
+                               a.q_heads, a.kv_heads, a.kv_len, n_split, tpw, scale_log2e);
+        else
+            hipLaunchKernelGGL((slim_decode_int8_gqa_kernel<64, true>), grid, dim3(64 * kGqaWaves), 0, stream,
+                               (const uint16_t*)a.q, a.k_codes, a.k_scale, a.v_codes, a.v_scale, ws_acc, ws_ml, a.kv_lens,
+                               a.q_heads, a.kv_heads, a.kv_len, n_split, tpw, scale_log2e);
+        return hipGetLastError();
+    }
     if (a.head_dim == 128)
         hipLaunchKernelGGL(slim_decode_int8_gqa_kernel<128>, grid, dim3(64 * kGqaWaves), 0, stream,
                            (const uint16_t*)a.q, a.k_codes, a.k_scale, a.v_codes, a.v_scale, ws_acc, ws_ml, a.kv_lens,

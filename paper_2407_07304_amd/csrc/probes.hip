@@ -3,6 +3,7 @@
 #include "../../include/slimprobe.h"
 
 #include "slim_common.h"
+#include "slim_kernels.h"
 
 namespace slim {
 
@@ -122,6 +123,36 @@ int slim_probe_mfma_bf16(const void* a, const void* b, int slices, float* out, i
     hipLaunchKernelGGL(slim::probe_mfma_bf16_kernel, dim3((unsigned)workgroups), dim3(256), 0, (hipStream_t)stream,
                        (const slim::u32x4*)a, (const slim::u32x4*)b, slices, out, iters);
     return hipGetLastError() == hipSuccess ? 0 : 2;
+}
+
+int slim_probe_gqa_decode_traffic(const void* q_bf16, const int8_t* k_codes, const float* k_scale, const int8_t* v_codes,
+                                  const float* v_scale, void* workspace, size_t workspace_bytes, int batch, int q_heads,
+                                  int kv_heads, int kv_len, int head_dim, void* stream) {
+    if (!q_bf16 || !k_codes || !k_scale || !v_codes || !v_scale || !workspace) return 1;
+    if (batch <= 0 || q_heads <= 0 || kv_heads <= 0 || kv_len <= 0 || (head_dim != 64 && head_dim != 128)) return 1;
+    if (q_heads % kv_heads != 0 || q_heads / kv_heads < 2 || q_heads / kv_heads > 32) return 1;   // the shapes the grouped kernel serves
+    if (misaligned(q_bf16) || misaligned(k_codes) || misaligned(k_scale) || misaligned(v_codes) || misaligned(v_scale) || misaligned(workspace)) return 1;
+    const int n_split = slim::decode_gqa_num_splits(kv_len, (long)batch * kv_heads);
+    const size_t n_part = (size_t)batch * q_heads * n_split;
+    if (workspace_bytes < n_part * ((size_t)head_dim + 2) * sizeof(float)) return 1;
+    slim::DecodeArgs a;
+    a.q = q_bf16;
+    a.k_codes = k_codes;
+    a.k_scale = k_scale;
+    a.v_codes = v_codes;
+    a.v_scale = v_scale;
+    a.out = nullptr;
+    a.workspace = (float*)workspace;
+    a.kv_lens = nullptr;
+    a.batch = batch;
+    a.q_heads = q_heads;
+    a.kv_heads = kv_heads;
+    a.kv_len = kv_len;
+    a.head_dim = head_dim;
+    a.softmax_scale = 1.0f;
+    (void)hipGetLastError();
+    const hipError_t e = slim::launch_decode_gqa_split(a, a.workspace, a.workspace + n_part * head_dim, n_split, (hipStream_t)stream, true);
+    return e == hipSuccess ? 0 : 2;
 }
 
 }  // extern "C"

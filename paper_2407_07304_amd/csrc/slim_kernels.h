@@ -55,7 +55,9 @@ int decode_num_splits(int kv_len, long n_bh);
 bool decode_uses_gqa_kernel(int q_heads, int kv_heads);
 int decode_gqa_tokens_per_wave(int kv_len, long n_bg);
 int decode_gqa_num_splits(int kv_len, long n_bg);
-hipError_t launch_decode_gqa_split(const DecodeArgs& a, float* ws_acc, float* ws_ml, int n_split, hipStream_t stream);
+// traffic_only: the measurement form (the kernel's loads without its arithmetic; what it writes is meaningless)
+hipError_t launch_decode_gqa_split(const DecodeArgs& a, float* ws_acc, float* ws_ml, int n_split, hipStream_t stream,
+                                   bool traffic_only = false);
 size_t decode_workspace_bytes(int batch, int q_heads, int kv_heads, int kv_len, int head_dim);
 hipError_t launch_decode(const DecodeArgs& a, hipStream_t stream);
 // The library's own decode scratch (one static device array per GPU) for the entry point that may not

@@ -22,6 +22,8 @@ def load():
         lib.slim_probe_quant_traffic.restype = i
         lib.slim_probe_mfma_bf16.argtypes = [p, p, i, p, i, i, p]
         lib.slim_probe_mfma_bf16.restype = i
+        lib.slim_probe_gqa_decode_traffic.argtypes = [p, p, p, p, p, p, ctypes.c_size_t, i, i, i, i, i, p]
+        lib.slim_probe_gqa_decode_traffic.restype = i
         _lib = lib
     return _lib
 
@@ -57,3 +59,14 @@ def slim_probe_mfma_bf16(a, b, out, workgroups, iters):
     _check(load().slim_probe_mfma_bf16(ctypes.c_void_p(a.data_ptr()), ctypes.c_void_p(b.data_ptr()), slices,
                                        ctypes.c_void_p(out.data_ptr()), workgroups, iters, _stream()),
            "slim_probe_mfma_bf16")
+
+
+def slim_probe_gqa_decode_traffic(q, k_codes, k_scale, v_codes, v_scale, workspace):
+    """Shapes as for slim_attn_decode_int8; workspace: a uint8 tensor of at least the decode's workspace size."""
+    B, Hq, _, D = q.shape
+    Hkv, T = k_codes.shape[1], k_codes.shape[2]
+    _check(load().slim_probe_gqa_decode_traffic(ctypes.c_void_p(q.data_ptr()), ctypes.c_void_p(k_codes.data_ptr()),
+                                                ctypes.c_void_p(k_scale.data_ptr()), ctypes.c_void_p(v_codes.data_ptr()),
+                                                ctypes.c_void_p(v_scale.data_ptr()), ctypes.c_void_p(workspace.data_ptr()),
+                                                workspace.numel() * workspace.element_size(), B, Hq, Hkv, T, D, _stream()),
+           "slim_probe_gqa_decode_traffic")

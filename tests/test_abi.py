@@ -161,7 +161,7 @@ def test_probe_library_exports_what_its_header_declares():
     from paper_2407_07304_amd import probes
     text = re.sub(r"/\*.*?\*/", "", open(os.path.join(ROOT, "include", "slimprobe.h")).read(), flags=re.S)
     names = sorted(set(re.findall(r"\b(slim_probe_[a-z_0-9]+)\s*\(", text)))
-    assert names == ["slim_probe_mfma_bf16", "slim_probe_quant_traffic", "slim_probe_stream_read"]
+    assert names == ["slim_probe_gqa_decode_traffic", "slim_probe_mfma_bf16", "slim_probe_quant_traffic", "slim_probe_stream_read"]
     lib = probes.load()
     for n in names:
         assert getattr(lib, n) is not None
@@ -170,6 +170,8 @@ def test_probe_library_exports_what_its_header_declares():
     assert lib.slim_probe_stream_read(P(A), 1000, P(A), None) == 1
     assert lib.slim_probe_quant_traffic(P(A), P(A), P(A), 10, 96, None) == 1
     assert lib.slim_probe_mfma_bf16(P(A), P(A), 0, P(A), 1, 1, None) == 1
+    assert lib.slim_probe_gqa_decode_traffic(P(A), P(A), P(A), P(A), P(A), P(A), 16, 2, 64, 8, 8192, 128, None) == 1   # workspace too small
+    assert lib.slim_probe_gqa_decode_traffic(P(A), P(A), P(A), P(A), P(A), P(A), 1 << 30, 1, 4, 4, 100, 128, None) == 1     # not a grouped shape
 
 
 def test_prefill_emit_rejects_bad_arguments(lib):
