@@ -285,6 +285,36 @@ def test_kv_quant_bit_exact_every_bf16_value_against_many_scales(sa, oracle):
     _quant_both(sa, oracle, np.ascontiguousarray(bits))
 
 
+@pytest.mark.timeout(1200)
+def test_kv_quant_bit_exact_every_bf16_pair(sa, oracle):
+    # EVERY finite positive bf16 amax (32 639 of them, subnormal and huge ones included) with EVERY bf16 0 <= x <= amax
+    # (random signs): 5.3e8 quotients, the whole domain of the quantiser's per-value arithmetic, on the hardware's own
+    # reciprocal.  Rows are [amax, x_1 .. x_127]; processed in slices of the amax range to bound the host memory.
+    rng = np.random.default_rng(34)
+    edges = [1, 0x2000, 0x4000, 0x5000, 0x6000, 0x6800, 0x7000, 0x7800, 0x7f80]
+    total = 0
+    for lo, hi in zip(edges[:-1], edges[1:]):
+        n_rows = sum((ab + 1 + 126) // 127 for ab in range(lo, hi))
+        n_rows_pad = (n_rows + 3) // 4 * 4
+        bits = np.zeros((n_rows_pad, 128), dtype=np.uint16)
+        r = 0
+        for ab in range(lo, hi):
+            xs = np.arange(0, ab + 1, dtype=np.uint16)
+            k = (xs.size + 126) // 127
+            blk = np.zeros(k * 127, dtype=np.uint16)
+            blk[:xs.size] = xs
+            bits[r:r + k, 0] = ab
+            bits[r:r + k, 1:] = blk.reshape(k, 127)
+            r += k
+        assert r == n_rows
+        bits[:, 1:] |= (rng.integers(0, 2, (n_rows_pad, 127)).astype(np.uint16) << 15)
+        total += int(n_rows) * 127
+        print("kv_quant every pair: amax bits [0x%04x, 0x%04x), %d rows" % (lo, hi, n_rows), flush=True)
+        _quant_both(sa, oracle, np.ascontiguousarray(bits.reshape(1, 4, n_rows_pad // 4, 128)))
+        del bits
+    assert total >= 532_000_000
+
+
 def test_prefill_int8_with_all_zero_tokens(sa, oracle):
     # a token whose K (or V) row is all zeros quantises to scale 0 and codes 0: it must act as a zero vector
     rng = np.random.default_rng(62)
@@ -708,6 +738,59 @@ def test_prefill_strip_large_scores_repeats_and_long_sequences(sa, oracle):
     torch.cuda.synchronize()
     assert torch.equal(long_strip, long_plain)
     check_close(host_f64(long_strip), oracle.attn(q, k, v, 0.125, True), "strip entry point beyond its length")
+
+
+@pytest.mark.parametrize("i", range(12))
+def test_prefill_strip_seeded_random_shapes_and_scales(sa, oracle, i):
+    # lengths that are no multiple of a tile, a chunk or a row block, batches, head groupings and softmax scales mixed
+    c = _random_shape(200 + i)
+    rng = np.random.default_rng(5000 + i)
+    S = int(rng.choice([c["n"], c["n"] * 2 + 1, 1024 + c["n"]]))
+    scale = float(rng.choice([1.0 / math.sqrt(c["D"]), 0.02, 0.3, 1.0]))
+    print("strip prefill random shape", i, c, "S", S, "scale", scale, flush=True)
+    q = normal_bf16(rng, (c["B"], c["Hq"], S, c["D"]))
+    k, v = normal_bf16(rng, (c["B"], c["Hkv"], S, c["D"])), normal_bf16(rng, (c["B"], c["Hkv"], S, c["D"]))
+    od = torch.float32 if i & 1 else torch.bfloat16
+    out = sa.slim_attn_prefill_strip(dev_bf16(q), dev_bf16(k), dev_bf16(v), scale, c["causal"], out_dtype=od)
+    one = sa.slim_attn_prefill(dev_bf16(q), dev_bf16(k), dev_bf16(v), scale, c["causal"], out_dtype=od)
+    torch.cuda.synchronize()
+    want = oracle.attn(q, k, v, scale, c["causal"])
+    if scale <= 0.3:
+        check_close(host_f64(out), want, "strip prefill, random shape %d" % i)
+    else:
+        # sharp rows: held to the streamed kernel's own distance from the oracle plus the tolerance's slack
+        # (what the rounding of P to bf16 costs there is the same in both orders)
+        err, err_one = np.abs(host_f64(out) - want), np.abs(host_f64(one) - want)
+        assert np.isfinite(host_f64(out)).all() and err.max() <= max(2e-2, 1.5 * err_one.max()) and err.mean() <= 2e-3
+
+
+def test_non_finite_values_stay_inside_their_kv_head(sa, oracle):
+    # the documented contract: a non-finite value in a (batch, KV head)'s K, V or scales may spoil every output row of
+    # the query heads that read that KV head (masked keys take part in the matrix products with probability zero),
+    # and nothing else
+    rng = np.random.default_rng(98)
+    B, Hq, Hkv, S, D = 2, 4, 2, 300, 128
+    q, k, v = normal_bf16(rng, (B, Hq, S, D)), normal_bf16(rng, (B, Hkv, S, D)), normal_bf16(rng, (B, Hkv, S, D))
+    v_bad = v.copy()
+    v_bad[0, 0, 250, 7] = 0x7f80                                     # +inf in V of (batch 0, KV head 0), at a late key
+    scale = 1.0 / math.sqrt(D)
+    out = sa.slim_attn_prefill(dev_bf16(q), dev_bf16(k), dev_bf16(v_bad), scale, True)
+    torch.cuda.synchronize()
+    want = oracle.attn(q, k, v, scale, True)
+    got = host_f64(out)
+    clean = np.ones((B, Hq), dtype=bool)
+    clean[0, :2] = False                                             # query heads 0 and 1 of batch 0 read KV head 0
+    check_close(got[clean], want[clean], "heads that do not read the spoiled KV head")
+    kc, ks = oracle.kv_quant_int8(k)
+    vc, vs = oracle.kv_quant_int8(v)
+    vs_bad = vs.copy()
+    vs_bad[1, 1, 5] = np.inf
+    dec = sa.slim_attn_decode_int8(dev_bf16(np.ascontiguousarray(q[:, :, S - 1:S])), dev(kc), dev(ks), dev(vc), dev(vs_bad), scale)
+    torch.cuda.synchronize()
+    want_d = oracle.attn(np.ascontiguousarray(q[:, :, S - 1:S]), kc, vc, scale, False, k_scale=ks, v_scale=vs)
+    clean = np.ones((B, Hq), dtype=bool)
+    clean[1, 2:] = False
+    check_close(host_f64(dec)[clean], want_d[clean], "decode heads that do not read the spoiled KV head")
 
 
 # ---------------------------------------------------------------- sharp softmax: the arithmetic's own bound
