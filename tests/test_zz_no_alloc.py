@@ -67,3 +67,27 @@ def test_static_scratch_decode_rejects_what_does_not_fit(sa):
     assert st == 5 and "workspace" in sa.status_string(st).lower()
     assert lib.slim_attn_decode_int8_static(None, A, A, A, A, A, 1, 2, 2, 10, D, 0, 0.1, None) == 1
     assert lib.slim_attn_decode_int8_static(A, A, A, A, A, A, 1, 2, 2, 10, 96, 0, 0.1, None) == 3
+
+
+def test_static_scratch_decode_under_graph_capture(sa, oracle):
+    # what the entry point is for: a decode step recorded into a HIP graph (nothing may allocate while a stream is
+    # being captured) and replayed; every replay, with eager work and synchronisations in between, must give the
+    # eager call's bits.  The first call on the device (which looks the scratch array's address up) comes before.
+    B, Hq, Hkv, T, D = 2, 16, 4, 3000, 128
+    args, ref, want = _case(sa, oracle, B, Hq, Hkv, T, D, 21)
+    eager = sa.slim_attn_decode_int8_static(*args).clone()
+    torch.cuda.synchronize()
+    assert torch.equal(eager, ref)
+    args[-1].zero_()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        sa.slim_attn_decode_int8_static(*args)
+    for rep in range(4):
+        args[-1].fill_(float(rep))                       # eager work between the replays
+        other = sa.slim_attn_decode_int8(*args[:6])      # ... including the decode that takes a workspace
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(args[-1], ref), "replay %d differs from the eager result" % rep
+        assert torch.equal(other, ref)
+    check_close(host_f64(args[-1]), want, "static-scratch decode replayed from a graph")
