@@ -50,6 +50,16 @@ __device__ __forceinline__ float strip_dpp(float v) {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
 }
 
+// Workgroup barrier for LDS traffic only: this wave's LDS reads and writes are done, then the barrier.  (Not
+// __syncthreads(): its fence would also wait for the global loads that are meant to stay in flight across it.  The
+// empty statements keep the compiler from moving memory accesses across.)
+__device__ __forceinline__ void strip_lds_barrier() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
 // NC: key columns the strip has room for (the sequence length rounded up, one of a few size classes)
 template <int D, int NC, bool OUT_F32>
 __global__ __launch_bounds__(256) void slim_prefill_strip_kernel(const StripParams p) {
@@ -117,15 +127,20 @@ __global__ __launch_bounds__(256) void slim_prefill_strip_kernel(const StripPara
         for (int s = 0; s < KS; ++s) dst[s] = __builtin_amdgcn_raw_buffer_load_b128(krs, off + 32 * s, 0, 0);
     };
     float m = kMasked;   // this wave's running row maximum (log2 units), the same in both halves of the wave
-    u32x4 kf[2][KS];
-    if (w < n_tiles) load_k(w, kf[0]);
-    auto score_tile = [&](int t, const u32x4 (&kfr)[KS]) {
+    // (one wave per SIMD and nothing else to hide the loads behind: three tiles' fragments are in flight per wave)
+    constexpr int KDEPTH = 3;
+    u32x4 kf[KDEPTH][KS];
+#pragma unroll
+    for (int j = 0; j < KDEPTH; ++j)
+        if (w + 4 * j < n_tiles) load_k(w + 4 * j, kf[j]);
+    auto score_tile = [&](int t, u32x4 (&kfr)[KS]) {
         f32x16 acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0.0f;
 #pragma unroll
         for (int s = 0; s < KS; ++s)
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kfr[s]), qreg[s], acc, 0, 0, 0);
+        if (t + 4 * KDEPTH < n_tiles) load_k(t + 4 * KDEPTH, kfr);   // the registers are free again: the tile three turns ahead
         // register r of this lane is key 32 t + 8 (r/4) + 4 hh + r%4 of query row my_q
         const int rel = lim - (t * kStripTile + 4 * hh);   // keys of this lane up to offset rel are visible
         float u[16];
@@ -145,13 +160,10 @@ __global__ __launch_bounds__(256) void slim_prefill_strip_kernel(const StripPara
             *reinterpret_cast<f16x4*>(strip + l32 * SROW + (t * kStripTile + 8 * r4 + 4 * hh) * 2) = hv;
         }
     };
-    for (int t = w; t < n_tiles; t += 8) {   // two tiles per turn: the next tile's K is in flight while this one is used
-        if (t + 4 < n_tiles) load_k(t + 4, kf[1]);
-        score_tile(t, kf[0]);
-        if (t + 4 < n_tiles) {
-            if (t + 8 < n_tiles) load_k(t + 8, kf[0]);
-            score_tile(t + 4, kf[1]);
-        }
+    for (int t = w; t < n_tiles; t += 4 * KDEPTH) {
+#pragma unroll
+        for (int j = 0; j < KDEPTH; ++j)
+            if (t + 4 * j < n_tiles) score_tile(t + 4 * j, kf[j]);
     }
     if (hh == 0) mS[w * 32 + l32] = m;   // (a wave without tiles leaves the stand-in for minus infinity)
     __syncthreads();
@@ -218,12 +230,15 @@ __global__ __launch_bounds__(256) void slim_prefill_strip_kernel(const StripPara
             v_addr[i] = (kStripTile * tp + rv) * ROWLV + (4 * (DTW * dh + i) + 2 * ((l >> 4) & 1) + ((l & 3) >> 1)) * 16 + 8 * (l & 1);
     }
     const int n_chunks = (n_keys + kStripChunk - 1) / kStripChunk;
-    u32x4 vst[NPV];
-    load_v(0, vst);
-    for (int ch = 0; ch < n_chunks; ++ch) {
-        store_v(vst);
-        __syncthreads();
-        if (ch + 1 < n_chunks) load_v(ch + 1, vst);
+    constexpr int VDEPTH = 3;   // chunks in registers ahead of the one in LDS
+    u32x4 vst[VDEPTH][NPV];
+#pragma unroll
+    for (int j = 0; j < VDEPTH; ++j)
+        if (j < n_chunks) load_v(j, vst[j]);
+    auto chunk = [&](int ch, u32x4 (&vreg)[NPV]) {
+        store_v(vreg);
+        strip_lds_barrier();
+        if (ch + VDEPTH < n_chunks) load_v(ch + VDEPTH, vreg);
         const int kb = ch * kStripChunk + kStripTile * tp;   // first key of this wave's tile
         if (kb < n_keys) {
 #pragma unroll
@@ -240,7 +255,12 @@ __global__ __launch_bounds__(256) void slim_prefill_strip_kernel(const StripPara
                 }
             }
         }
-        __syncthreads();   // everyone is done with this chunk before the next one replaces it
+        strip_lds_barrier();   // everyone is done with this chunk before the next one replaces it
+    };
+    for (int ch = 0; ch < n_chunks; ch += VDEPTH) {
+#pragma unroll
+        for (int j = 0; j < VDEPTH; ++j)
+            if (ch + j < n_chunks) chunk(ch + j, vst[j]);
     }
 
     // ---- the two tile parities of each half are added (through the strip's place: the strip is dead), divided by
