@@ -37,7 +37,7 @@
 //   - Under the causal mask a workgroup takes the row-block pair (x, n-1-x) one after the
 //     other, so every workgroup does the same amount of work.  The short block goes first: the
 //     key tiles it read are still in the L2 when the long block starts over at tile 0 (the other
-//     order re-fetched them: 81.5 MB of HBM traffic on B=1, H=32, S=2048 against 67.4 MB now,
+//     order re-fetched them: 81.5 MB of HBM traffic on B=1, H=32, S=2048 against 68.8 MB now,
 //     which is Q, K, V and O once each).
 #include <type_traits>
 
