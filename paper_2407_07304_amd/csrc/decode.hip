@@ -27,6 +27,7 @@ namespace slim {
 
 constexpr int kDecodeWaves = 4;
 constexpr int kChunk = 64;   // tokens per wave per chunk
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 // lane exchange inside a slot via DPP (no LDS traffic); every lane of the slot ends with the slot total
 template <int CTRL>
@@ -222,27 +223,49 @@ __global__ __launch_bounds__(256) void slim_decode_int8_split_kernel(
     }
 }
 
-// Merges the n_split partial (max, sum, accumulator) triples of one (batch, head) in
-// split order and writes the bf16 output row.  The loops are unrolled by eight so that eight
-// splits' loads are in flight at a time: with many splits (short batches of long caches)
-// a loop that waits for every load costs more than the split kernel itself.
+// Merges the n_split partial (max, sum, accumulator) triples of one (batch, head) in split order and writes the
+// bf16 output row.  The launch is latency-bound (a few kilobytes per workgroup, just written by the split kernel),
+// so all loads of up to kCombineChunk splits are issued before anything is computed: one round trip to memory
+// instead of one for the maxima and another for the sums and accumulators.  More splits than that (short batches of
+// long caches) are merged a chunk at a time with a running (max, sum, accumulator), still in split order.  Slots
+// past the last split re-read the last one and count as empty (max = kMasked, sum = 0).
+constexpr int kCombineChunk = 16;
+
 template <int D>
 __global__ __launch_bounds__(D) void slim_decode_combine_kernel(const float* __restrict__ ws_acc,
                                                                 const float* __restrict__ ws_ml,
                                                                 uint16_t* __restrict__ out, int n_split) {
+    constexpr int CH = kCombineChunk;
     const long bh = blockIdx.x;
     const int d = threadIdx.x;
     const float* const ml = ws_ml + bh * n_split * 2;
     const float* const acc = ws_acc + bh * n_split * D + d;
-    float M = kMasked;
-#pragma unroll 8
-    for (int sp = 0; sp < n_split; ++sp) M = fmaxf(M, ml[2 * sp]);
-    float L = 0.0f, o = 0.0f;
-#pragma unroll 8
-    for (int sp = 0; sp < n_split; ++sp) {
-        const float f = fast_exp2(ml[2 * sp] - M);
-        L = fmaf(f, ml[2 * sp + 1], L);
-        o = fmaf(f, acc[(long)sp * D], o);
+    float M = kMasked, L = 0.0f, o = 0.0f;
+    for (int s0 = 0; s0 < n_split; s0 += CH) {
+        float m[CH], l[CH], a[CH];
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const int sp = min(s0 + i, n_split - 1);
+            const bool there = s0 + i < n_split;
+            const f32x2 t = *reinterpret_cast<const f32x2*>(ml + 2 * sp);
+            const float av = acc[(long)sp * D];
+            m[i] = there ? t[0] : kMasked;
+            l[i] = there ? t[1] : 0.0f;
+            a[i] = there ? av : 0.0f;
+        }
+        float m_new = M;
+#pragma unroll
+        for (int i = 0; i < CH; ++i) m_new = fmaxf(m_new, m[i]);
+        const float keep = fast_exp2(M - m_new);   // first chunk: L = o = 0, whatever this is
+        L *= keep;
+        o *= keep;
+#pragma unroll
+        for (int i = 0; i < CH; ++i) {
+            const float f = fast_exp2(m[i] - m_new);   // an empty split has sum = 0 and accumulator = 0
+            L = fmaf(f, l[i], L);
+            o = fmaf(f, a[i], o);
+        }
+        M = m_new;
     }
     out[bh * D + d] = (uint16_t)(pack_bf16x2(o / L, 0.0f) & 0xffffu);
 }
