@@ -554,6 +554,62 @@ def test_calls_follow_the_current_stream(sa, oracle):
         assert torch.equal(a, b)
 
 
+def test_every_entry_point_replays_from_a_hip_graph(sa, oracle):
+    # no entry point allocates, synchronises or clears memory with a memset node: a whole serving step (build the
+    # cache, prefill over it, the comparison variants, append a token, decode) recorded into one HIP graph gives, on
+    # every replay, with eager work and synchronisations in between, the bits of the eager calls
+    rng = np.random.default_rng(97)
+    B, Hq, Hkv, S, D = 1, 8, 2, 520, 128
+    q, k, v = (dev_bf16(normal_bf16(rng, shp)) for shp in ((B, Hq, S, D), (B, Hkv, S, D), (B, Hkv, S, D)))
+    k_new, v_new = (dev_bf16(normal_bf16(rng, (B, Hkv, 1, D))) for _ in range(2))
+    q1 = q[:, :, S - 1:S].contiguous()
+    scale = 1.0 / math.sqrt(D)
+    pos = torch.full((B,), S - 1, dtype=torch.int32, device="cuda")
+    lens = torch.full((B,), S, dtype=torch.int32, device="cuda")
+    ws = torch.empty((sa.slim_attn_decode_int8_workspace_bytes(B, Hq, Hkv, S, D),), dtype=torch.uint8, device="cuda")
+    ws2 = torch.empty((B * Hq * S * 2,), dtype=torch.float32, device="cuda")
+
+    def buffers():
+        return {"kc": torch.empty((B, Hkv, S, D), dtype=torch.int8, device="cuda"),
+                "ks": torch.empty((B, Hkv, S), dtype=torch.float32, device="cuda"),
+                "vc": torch.empty((B, Hkv, S, D), dtype=torch.int8, device="cuda"),
+                "vs": torch.empty((B, Hkv, S), dtype=torch.float32, device="cuda"),
+                "pre": torch.empty_like(q), "pre8": torch.empty_like(q), "two": torch.empty_like(q),
+                "strip": torch.empty_like(q), "dec": torch.empty_like(q1), "var": torch.empty_like(q1),
+                "stat": torch.empty_like(q1)}
+
+    def step(o):
+        sa.kv_quant_int8(k, o["kc"], o["ks"])
+        sa.kv_quant_int8(v, o["vc"], o["vs"])
+        sa.slim_attn_prefill(q, k, v, scale, True, out=o["pre"])
+        sa.slim_attn_prefill(q, o["kc"], o["vc"], scale, True, k_scale=o["ks"], v_scale=o["vs"], out=o["pre8"])
+        sa.slim_attn_prefill_two_sweep(q, k, v, scale, True, out=o["two"], workspace=ws2)
+        sa.slim_attn_prefill_strip(q, k, v, scale, True, out=o["strip"])
+        sa.kv_quant_int8_append(k_new, o["kc"], o["ks"], pos)
+        sa.kv_quant_int8_append(v_new, o["vc"], o["vs"], pos)
+        sa.slim_attn_decode_int8(q1, o["kc"], o["ks"], o["vc"], o["vs"], scale, out=o["dec"], workspace=ws)
+        sa.slim_attn_decode_int8_varlen(q1, o["kc"], o["ks"], o["vc"], o["vs"], lens, scale, out=o["var"], workspace=ws)
+        sa.slim_attn_decode_int8_static(q1, o["kc"], o["ks"], o["vc"], o["vs"], scale, o["stat"])
+
+    ref = buffers()
+    step(ref)
+    torch.cuda.synchronize()
+    assert torch.equal(ref["dec"], ref["var"]) and torch.equal(ref["dec"], ref["stat"])
+    got = buffers()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step(got)
+    for rep in range(3):
+        for name, t in got.items():                       # eager work between the replays: every output is spoiled
+            t.fill_(1) if t.dtype == torch.int8 else t.fill_(float("nan"))
+        sa.slim_attn_decode_int8(q1, ref["kc"], ref["ks"], ref["vc"], ref["vs"], scale, workspace=ws)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name in ref:
+            assert torch.equal(got[name].view(torch.uint8), ref[name].view(torch.uint8)), "replay %d: %s differs" % (rep, name)
+
+
 def _loaded_hip_runtime():
     """The HIP runtime this process already has mapped (the one the library and torch call into)."""
     import ctypes
