@@ -9,8 +9,8 @@
  *                          keys, softmax over the row, row times V), bf16 or INT8 K/V
  *   slim_attn_decode_int8  next-token attention over the INT8 cache (section 2.2)
  *
- * and, around them, what a serving loop needs: kv_quant_int8_append (one new token per
- * sequence into the cache), slim_attn_prefill_emit_int8 (prefill that also writes the
+ * and, around them, what a serving loop needs: kv_quant_int8_pair (K and V in one launch),
+ * kv_quant_int8_append (one new token per sequence into the cache), slim_attn_prefill_emit_int8 (prefill that also writes the
  * cache), slim_attn_decode_int8_varlen (a batch whose caches differ in length), plus
  * slim_attn_prefill_two_sweep and slim_attn_prefill_strip, two comparison variants of the prefill that keep the
  * paper's own order of operations (the whole score row before the softmax).
@@ -71,6 +71,21 @@ enum { SLIM_BF16 = 0, SLIM_F32 = 1, SLIM_I8 = 2 };
 int kv_quant_int8(const void* x_bf16, int8_t* codes, float* scales,
                   int batch, int q_heads, int kv_heads, int seq_len, int head_dim,
                   int causal, float softmax_scale, void* stream);
+
+/*
+ * kv_quant_int8 on the K and the V of a cache in one launch (section 2.2 quantises both the same
+ * way): k_codes/k_scale are what kv_quant_int8 gives on k_bf16, v_codes/v_scale what it gives on
+ * v_bf16, bit for bit.  For the tensors of a single prefill a call is bound by the launch, and the
+ * pair takes little more than one of the two single calls.
+ * k_bf16, v_bf16     device, in   [batch, kv_heads, seq_len, head_dim] bf16 each
+ * k_codes, v_codes   device, out  [batch, kv_heads, seq_len, head_dim] int8 each
+ * k_scale, v_scale   device, out  [batch, kv_heads, seq_len] fp32 each
+ * The six buffers must not overlap.  Argument tail and errors as in kv_quant_int8.
+ */
+int kv_quant_int8_pair(const void* k_bf16, const void* v_bf16, int8_t* k_codes, float* k_scale,
+                       int8_t* v_codes, float* v_scale,
+                       int batch, int q_heads, int kv_heads, int seq_len, int head_dim,
+                       int causal, float softmax_scale, void* stream);
 
 /*
  * Appends one token per sequence to an INT8 cache: the step before a decode over it

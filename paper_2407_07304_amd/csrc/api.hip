@@ -73,6 +73,24 @@ int kv_quant_int8(const void* x_bf16, int8_t* codes, float* scales, int batch, i
     return e == hipSuccess ? SLIM_OK : SLIM_ERR_LAUNCH;
 }
 
+int kv_quant_int8_pair(const void* k_bf16, const void* v_bf16, int8_t* k_codes, float* k_scale, int8_t* v_codes,
+                       float* v_scale, int batch, int q_heads, int kv_heads, int seq_len, int head_dim, int causal,
+                       float softmax_scale, void* stream) {
+    if (!k_bf16 || !v_bf16 || !k_codes || !k_scale || !v_codes || !v_scale) return SLIM_ERR_NULL;
+    const int st = check_shape(batch, kv_heads, kv_heads, seq_len, head_dim);
+    if (st != SLIM_OK) return st;
+    const int st_tail = check_unused_tail(q_heads, kv_heads, causal, softmax_scale);
+    if (st_tail != SLIM_OK) return st_tail;
+    if (misaligned(k_bf16) || misaligned(v_bf16) || misaligned(k_codes) || misaligned(k_scale) || misaligned(v_codes) ||
+        misaligned(v_scale))
+        return SLIM_ERR_ALIGN;
+    const long n_rows = (long)batch * kv_heads * seq_len;
+    drop_stale_hip_error();
+    const hipError_t e = slim::launch_kv_quant_int8_pair(k_bf16, v_bf16, k_codes, k_scale, v_codes, v_scale, n_rows, head_dim,
+                                                         (hipStream_t)stream);
+    return e == hipSuccess ? SLIM_OK : SLIM_ERR_LAUNCH;
+}
+
 int kv_quant_int8_append(const void* x_new_bf16, int8_t* codes, float* scales, const int32_t* positions, int batch,
                          int q_heads, int kv_heads, int kv_len, int head_dim, int causal, float softmax_scale,
                          void* stream) {

@@ -18,8 +18,8 @@ namespace slim {
 // be what the next kernel reads again (the K/V of a prefill): it is left to the caches, one row per thread, which
 // finishes a launch-bound call soonest.
 template <int D, bool STREAM, int U>
-__global__ __launch_bounds__(256) void kv_quant_int8_kernel(const uint16_t* __restrict__ x, int8_t* __restrict__ codes,
-                                                            float* __restrict__ scales, long n_rows) {
+__device__ __forceinline__ void kv_quant_rows(const uint16_t* __restrict__ x, int8_t* __restrict__ codes,
+                                              float* __restrict__ scales, long n_rows) {
     constexpr int LPR = D / 8;           // lanes per row
     constexpr int ROWS = 256 / LPR;      // rows per workgroup and load
     const int lane_in_row = threadIdx.x % LPR;
@@ -48,6 +48,26 @@ __global__ __launch_bounds__(256) void kv_quant_int8_kernel(const uint16_t* __re
             }
         }
     }
+}
+
+template <int D, bool STREAM, int U>
+__global__ __launch_bounds__(256) void kv_quant_int8_kernel(const uint16_t* __restrict__ x, int8_t* __restrict__ codes,
+                                                            float* __restrict__ scales, long n_rows) {
+    kv_quant_rows<D, STREAM, U>(x, codes, scales, n_rows);
+}
+
+// Two tensors of the same shape in one launch (the K and the V of a cache): blockIdx.y picks the tensor.  On
+// inputs of a few megabytes a call is launch-bound, and one launch does the work of two in little more than the
+// time of one.
+struct QuantPair {
+    const uint16_t* x[2];
+    int8_t* codes[2];
+    float* scales[2];
+};
+template <int D, bool STREAM, int U>
+__global__ __launch_bounds__(256) void kv_quant_int8_pair_kernel(const QuantPair p, long n_rows) {
+    const int t = (int)blockIdx.y;   // uniform
+    kv_quant_rows<D, STREAM, U>(t == 0 ? p.x[0] : p.x[1], t == 0 ? p.codes[0] : p.codes[1], t == 0 ? p.scales[0] : p.scales[1], n_rows);
 }
 
 // One new token per (batch, KV head): row r = b * Hkv + g of x goes to token positions[b] of that head's cache.
@@ -87,6 +107,31 @@ hipError_t launch_kv_quant_int8(const void* x, int8_t* codes, float* scales, lon
     } else {
         if (stream_in) hipLaunchKernelGGL((kv_quant_int8_kernel<64, true, 4>), grid, block, 0, stream, (const uint16_t*)x, codes, scales, n_rows);
         else hipLaunchKernelGGL((kv_quant_int8_kernel<64, false, 1>), grid, block, 0, stream, (const uint16_t*)x, codes, scales, n_rows);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_kv_quant_int8_pair(const void* k, const void* v, int8_t* k_codes, float* k_scale, int8_t* v_codes,
+                                     float* v_scale, long n_rows, int head_dim, hipStream_t stream) {
+    const bool stream_in = 2 * n_rows * head_dim * 3 > (256L << 20);   // both inputs + both code tensors beyond the last-level cache
+    const int rows_per_block = 256 / (head_dim / 8) * (stream_in ? 4 : 1);
+    long blocks = (n_rows + rows_per_block - 1) / rows_per_block;
+    const long max_blocks = 1L << 20;
+    if (blocks > max_blocks) blocks = max_blocks;
+    const dim3 grid((unsigned)blocks, 2u), block(256);
+    QuantPair p;
+    p.x[0] = (const uint16_t*)k;
+    p.x[1] = (const uint16_t*)v;
+    p.codes[0] = k_codes;
+    p.codes[1] = v_codes;
+    p.scales[0] = k_scale;
+    p.scales[1] = v_scale;
+    if (head_dim == 128) {
+        if (stream_in) hipLaunchKernelGGL((kv_quant_int8_pair_kernel<128, true, 4>), grid, block, 0, stream, p, n_rows);
+        else hipLaunchKernelGGL((kv_quant_int8_pair_kernel<128, false, 1>), grid, block, 0, stream, p, n_rows);
+    } else {
+        if (stream_in) hipLaunchKernelGGL((kv_quant_int8_pair_kernel<64, true, 4>), grid, block, 0, stream, p, n_rows);
+        else hipLaunchKernelGGL((kv_quant_int8_pair_kernel<64, false, 1>), grid, block, 0, stream, p, n_rows);
     }
     return hipGetLastError();
 }

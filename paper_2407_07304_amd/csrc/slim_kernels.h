@@ -9,6 +9,8 @@ namespace slim {
 hipError_t launch_kv_quant_int8(const void* x, int8_t* codes, float* scales, long n_rows, int head_dim,
                                 hipStream_t stream);
 
+hipError_t launch_kv_quant_int8_pair(const void* k, const void* v, int8_t* k_codes, float* k_scale, int8_t* v_codes,
+                                     float* v_scale, long n_rows, int head_dim, hipStream_t stream);
 hipError_t launch_kv_quant_int8_append(const void* x, int8_t* codes, float* scales, const int* positions, int batch,
                                        int kv_heads, int kv_len, int head_dim, hipStream_t stream);
 

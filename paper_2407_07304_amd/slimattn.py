@@ -35,6 +35,8 @@ def load():
         p, i, f = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
         lib.kv_quant_int8.argtypes = [p, p, p, i, i, i, i, i, i, f, p]
         lib.kv_quant_int8.restype = i
+        lib.kv_quant_int8_pair.argtypes = [p, p, p, p, p, p, i, i, i, i, i, i, f, p]
+        lib.kv_quant_int8_pair.restype = i
         lib.kv_quant_int8_append.argtypes = [p, p, p, p, i, i, i, i, i, i, f, p]
         lib.kv_quant_int8_append.restype = i
         lib.slim_attn_prefill.argtypes = [p, p, p, p, p, p, i, i, i, i, i, i, f, i, i, p]
@@ -97,6 +99,24 @@ def kv_quant_int8(x, codes=None, scales=None):
     _check(load().kv_quant_int8(_ptr(x, torch.bfloat16), _ptr(codes, torch.int8), _ptr(scales, torch.float32),
                                 B, Hkv, Hkv, S, D, 0, 1.0, _stream()))
     return codes, scales
+
+
+def kv_quant_int8_pair(k, v, k_codes=None, k_scale=None, v_codes=None, v_scale=None):
+    """kv_quant_int8 on k and v [B,Hkv,S,D] bf16 in one launch -> (k_codes, k_scale, v_codes, v_scale)."""
+    B, Hkv, S, D = k.shape
+    assert v.shape == k.shape
+    outs = []
+    for codes, scales in ((k_codes, k_scale), (v_codes, v_scale)):
+        if codes is None:
+            codes = torch.empty((B, Hkv, S, D), dtype=torch.int8, device=k.device)
+        if scales is None:
+            scales = torch.empty((B, Hkv, S), dtype=torch.float32, device=k.device)
+        assert codes.shape == (B, Hkv, S, D) and scales.shape == (B, Hkv, S)
+        outs += [codes, scales]
+    _check(load().kv_quant_int8_pair(_ptr(k, torch.bfloat16), _ptr(v, torch.bfloat16), _ptr(outs[0], torch.int8),
+                                     _ptr(outs[1], torch.float32), _ptr(outs[2], torch.int8), _ptr(outs[3], torch.float32),
+                                     B, Hkv, Hkv, S, D, 0, 1.0, _stream()))
+    return tuple(outs)
 
 
 def slim_attn_prefill(q, k, v, softmax_scale, causal=True, k_scale=None, v_scale=None, out=None,

@@ -27,6 +27,9 @@ int main() {
     expect(kv_quant_int8(A, A8, Af, 1, 1, 1, 4, 128, 0, nan, nullptr), SLIM_ERR_SHAPE, "quant scale");
     expect(kv_quant_int8(A, static_cast<int8_t*>(M), Af, 1, 1, 1, 4, 128, 0, 1.0f, nullptr), SLIM_ERR_ALIGN, "quant align");
     expect(kv_quant_int8(A, A8, Af, 65536, 65536, 65536, 2147483647, 128, 0, 1.0f, nullptr), SLIM_ERR_SHAPE, "quant overflowing sizes");
+    expect(kv_quant_int8_pair(A, nullptr, A8, Af, A8, Af, 1, 1, 1, 4, 128, 0, 1.0f, nullptr), SLIM_ERR_NULL, "pair null");
+    expect(kv_quant_int8_pair(A, A, A8, Af, static_cast<int8_t*>(M), Af, 1, 1, 1, 4, 128, 0, 1.0f, nullptr), SLIM_ERR_ALIGN, "pair align");
+    expect(kv_quant_int8_pair(A, A, A8, Af, A8, Af, 1, 3, 2, 4, 128, 0, 1.0f, nullptr), SLIM_ERR_SHAPE, "pair head ratio");
     expect(kv_quant_int8_append(A, A8, Af, nullptr, 1, 1, 1, 4, 128, 0, 1.0f, nullptr), SLIM_ERR_NULL, "append null");
     expect(kv_quant_int8_append(A, A8, Af, static_cast<const int32_t*>(reinterpret_cast<void*>(0x1002)), 1, 1, 1, 4, 128, 0, 1.0f, nullptr), SLIM_ERR_ALIGN, "append align");
     expect(slim_attn_prefill(A, A, A, nullptr, nullptr, nullptr, 1, 2, 2, 16, 128, 1, 0.1f, SLIM_BF16, SLIM_BF16, nullptr), SLIM_ERR_NULL, "prefill null");

@@ -27,7 +27,7 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert {"kv_quant_int8", "slim_attn_prefill", "slim_attn_decode_int8", "slim_attn_decode_int8_varlen",
-            "kv_quant_int8_append", "slim_attn_prefill_emit_int8", "slim_attn_decode_int8_workspace_bytes", "slim_status_string",
+            "kv_quant_int8_append", "kv_quant_int8_pair", "slim_attn_prefill_emit_int8", "slim_attn_decode_int8_workspace_bytes", "slim_status_string",
             "slim_attn_prefill_two_sweep", "slim_attn_prefill_two_sweep_workspace_bytes", "slim_attn_prefill_strip",
             "slim_attn_prefill_strip_max_seq_len", "slim_attn_decode_int8_static", "slim_attn_decode_int8_static_max_bytes"} <= set(names)
     for n in names:
@@ -113,6 +113,19 @@ def test_varlen_decode_rejects_bad_arguments(lib):
     assert call(lens=A + 2) == 4 and call(q=A + 4) == 4
     assert call(T=0) == 2 and call(D=96) == 3
     assert call(wsb=8) == 5
+
+
+def test_quant_pair_rejects_bad_arguments(lib):
+    f = lib.kv_quant_int8_pair
+
+    def call(k=A, v=A, kc=A, ks=A, vc=A, vs=A, B=2, Hq=2, Hkv=2, S=100, D=128, causal=0, scale=1.0):
+        return f(P(k), P(v), P(kc), P(ks), P(vc), P(vs), B, Hq, Hkv, S, D, causal, scale, None)
+
+    assert call(k=None) == 1 and call(v=None) == 1 and call(vs=None) == 1 and call(kc=None) == 1
+    assert call(S=0) == 2 and call(B=-1) == 2
+    assert call(D=96) == 3
+    assert call(v=A + 8) == 4 and call(vc=A + 4) == 4
+    assert call(Hq=3) == 2 and call(causal=2) == 2 and call(scale=0.0) == 2
 
 
 def test_append_rejects_bad_arguments(lib):

@@ -61,6 +61,24 @@ def test_kv_quant_bit_exact_special_rows(sa, oracle):
 
 
 @pytest.mark.timeout(600)
+@pytest.mark.parametrize("shape", [(2, 3, 301, 128), (1, 2, 77, 64), (1, 1, 1, 128), (1, 32, 2048, 128), (4, 32, 3000, 128)])
+def test_kv_quant_pair_gives_the_single_calls_bits(sa, oracle, shape):
+    # K and V in one launch: each tensor's codes and scales are the oracle's (the last shape is past the size at
+    # which the pair takes the streaming loads, the one before is C2's)
+    print("kv_quant pair", shape, flush=True)
+    rng = np.random.default_rng(34)
+    kb, vb = normal_bf16(rng, shape), normal_bf16(rng, shape)
+    vb[0, 0, 0] = 0                                                       # an all-zero row in the second tensor only
+    kb[-1, -1, -1] = rng.integers(0, 0x0080, shape[-1]).astype(np.uint16) # subnormals in the first tensor's last row
+    kc, ks, vc, vs = sa.kv_quant_int8_pair(dev_bf16(kb), dev_bf16(vb))
+    torch.cuda.synchronize()
+    for name, bits, codes, scales in (("K", kb, kc, ks), ("V", vb, vc, vs)):
+        want_c, want_s = oracle.kv_quant_int8(bits)
+        assert np.array_equal(scales.cpu().numpy().view(np.uint32), want_s.view(np.uint32)), name + " scales differ"
+        assert np.array_equal(codes.cpu().numpy(), want_c), name + " codes differ"
+
+
+@pytest.mark.timeout(600)
 def test_kv_quant_bit_exact_c3_shape(sa, oracle):
     w = WORKLOADS["C3"]
     print("kv_quant C3 K tensor", flush=True)
@@ -574,6 +592,10 @@ def test_every_entry_point_replays_from_a_hip_graph(sa, oracle):
                 "ks": torch.empty((B, Hkv, S), dtype=torch.float32, device="cuda"),
                 "vc": torch.empty((B, Hkv, S, D), dtype=torch.int8, device="cuda"),
                 "vs": torch.empty((B, Hkv, S), dtype=torch.float32, device="cuda"),
+                "kc2": torch.empty((B, Hkv, S, D), dtype=torch.int8, device="cuda"),
+                "ks2": torch.empty((B, Hkv, S), dtype=torch.float32, device="cuda"),
+                "vc2": torch.empty((B, Hkv, S, D), dtype=torch.int8, device="cuda"),
+                "vs2": torch.empty((B, Hkv, S), dtype=torch.float32, device="cuda"),
                 "pre": torch.empty_like(q), "pre8": torch.empty_like(q), "two": torch.empty_like(q),
                 "strip": torch.empty_like(q), "dec": torch.empty_like(q1), "var": torch.empty_like(q1),
                 "stat": torch.empty_like(q1)}
@@ -581,6 +603,7 @@ def test_every_entry_point_replays_from_a_hip_graph(sa, oracle):
     def step(o):
         sa.kv_quant_int8(k, o["kc"], o["ks"])
         sa.kv_quant_int8(v, o["vc"], o["vs"])
+        sa.kv_quant_int8_pair(k, v, o["kc2"], o["ks2"], o["vc2"], o["vs2"])
         sa.slim_attn_prefill(q, k, v, scale, True, out=o["pre"])
         sa.slim_attn_prefill(q, o["kc"], o["vc"], scale, True, k_scale=o["ks"], v_scale=o["vs"], out=o["pre8"])
         sa.slim_attn_prefill_two_sweep(q, k, v, scale, True, out=o["two"], workspace=ws2)
