@@ -13,11 +13,11 @@
 //           on the way (in-lane, then across the wave's halves, then across the waves).
 //   pass 2  softmax over the strip, in place: p = exp2(u - max) in fp32, summed in fp32, rounded to bf16 over
 //           the fp16 score it came from.  Pure vector work, all 256 threads.
-//   pass 3  strip times V.  V comes through LDS in 64-key chunks (coalesced 128-bit loads, the next chunk in
-//           registers while this one is used); wave w takes tile (w & 1) of the chunk and half (w >> 1) of the
-//           head dimension: O^T += V^T P^T with P^T read from the strip as it stands (B operand: lane = query,
-//           8 consecutive keys) and V^T through the LDS transpose read.  The two tile parities of a half are
-//           added at the end, divided by the row sum and stored.
+//   pass 3  strip times V.  Wave w takes tile (w & 1) of every 64-key chunk and half (w >> 1) of the head
+//           dimension, and brings in just that piece of V itself (128-bit loads, three chunks ahead in registers,
+//           an LDS region of its own, so no barriers): O^T += V^T P^T with P^T read from the strip as it stands
+//           (B operand: lane = query, 8 consecutive keys) and V^T through the LDS transpose read.  The two tile
+//           parities of a half are added at the end, divided by the row sum and stored.
 // A score waits in the strip as the fp16 of u - ref, ref being the wave's row maximum up to and including the
 // score's own tile: never positive, small exactly where the probability is not, so the 11 significant bits cost
 // less than 2^-11 of log2(1/p) in the exponent (at most 0.4 % of a probability near 2^-8, less above and nothing
@@ -50,16 +50,6 @@ __device__ __forceinline__ float strip_dpp(float v) {
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, false));
 }
 
-// Workgroup barrier for LDS traffic only: this wave's LDS reads and writes are done, then the barrier.  (Not
-// __syncthreads(): its fence would also wait for the global loads that are meant to stay in flight across it.  The
-// empty statements keep the compiler from moving memory accesses across.)
-__device__ __forceinline__ void strip_lds_barrier() {
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-}
-
 // NC: key columns the strip has room for (the sequence length rounded up, one of a few size classes)
 template <int D, int NC, bool OUT_F32>
 __global__ __launch_bounds__(256) void slim_prefill_strip_kernel(const StripParams p) {
@@ -68,9 +58,8 @@ __global__ __launch_bounds__(256) void slim_prefill_strip_kernel(const StripPara
     constexpr int DTW = DT / 2;         // of which a wave takes half
     constexpr int ROWB = 2 * D;         // bytes per K/V row in memory
     constexpr int SROW = 2 * NC + 16;   // strip row pitch: the padding shifts every row by 16 bytes, so the 128-bit reads of 16 rows meet 16 different bank groups
-    constexpr int ROWLV = 2 * D + 64;   // staged V row pitch (conflict-free transpose reads)
     constexpr int STRIP_BYTES = kStripRows * SROW;
-    constexpr int STAGE_BYTES = kStripChunk * ROWLV;
+    constexpr int STAGE_BYTES = 4 * kStripTile * (D + 32);   // V staging: a region of 32 half rows (padded) per wave
     constexpr int REF_BYTES = (NC / kStripTile) * 32 * 4;   // one reference per tile and row
     static_assert(NC % kStripChunk == 0, "the strip holds whole chunks");
     static_assert(STRIP_BYTES >= 2 * DTW * 16 * 64 * 4, "the partial outputs are merged in the strip's place");
@@ -197,22 +186,29 @@ __global__ __launch_bounds__(256) void slim_prefill_strip_kernel(const StripPara
     }
     __syncthreads();
 
-    // ---- pass 3: strip times V
+    // ---- pass 3: strip times V.  Wave (tp, dh) needs, of every 64-key chunk, the 32 keys of its tile parity and the
+    // half of the head dimension it accumulates: it loads exactly that piece (8 or 4 lanes per row, half a row each),
+    // stages it in an LDS region of its own and reads it back through the transpose read.  No other wave touches the
+    // region and LDS runs a wave's accesses in order, so the pass needs no barrier at all.
     const int tp = w & 1, dh = w >> 1;
-    constexpr int CPR = ROWB / 16;                       // 16-byte pieces per V row
-    constexpr int NPV = kStripChunk * CPR / 256;         // pieces per thread and chunk
+    constexpr int ROWW = D;                              // bytes of a V row a wave takes: half the head dimension
+    constexpr int LPRW = ROWW / 16;                      // lanes per row
+    constexpr int NPV = kStripTile * LPRW / 64;          // 128-bit loads per lane and chunk
+    constexpr int PITCH = ROWW + 32;                     // staged row pitch (spreads the transpose reads over the banks)
+    static_assert(4 * kStripTile * PITCH <= STAGE_BYTES, "the four waves' regions fit the staging buffer");
+    char* const mine = stage + w * (kStripTile * PITCH);
     auto load_v = [&](int ch, u32x4 (&dst)[NPV]) {
 #pragma unroll
         for (int i = 0; i < NPV; ++i) {
-            const int pid = tid + 256 * i, row = pid / CPR, col = pid % CPR;
-            dst[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (ch * kStripChunk + row) * ROWB + col * 16, 0, 0);
+            const int row = (64 / LPRW) * i + l / LPRW, col = l % LPRW;
+            dst[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (ch * kStripChunk + kStripTile * tp + row) * ROWB + ROWW * dh + col * 16, 0, 0);
         }
     };
     auto store_v = [&](const u32x4 (&src)[NPV]) {
 #pragma unroll
         for (int i = 0; i < NPV; ++i) {
-            const int pid = tid + 256 * i, row = pid / CPR, col = pid % CPR;
-            *reinterpret_cast<u32x4*>(stage + row * ROWLV + col * 16) = src[i];
+            const int row = (64 / LPRW) * i + l / LPRW, col = l % LPRW;
+            *reinterpret_cast<u32x4*>(mine + row * PITCH + col * 16) = src[i];
         }
     };
     f32x16 o[DTW];
@@ -227,7 +223,7 @@ __global__ __launch_bounds__(256) void slim_prefill_strip_kernel(const StripPara
         const int rv = 8 * hh + ((l & 15) >> 2);
 #pragma unroll
         for (int i = 0; i < DTW; ++i)
-            v_addr[i] = (kStripTile * tp + rv) * ROWLV + (4 * (DTW * dh + i) + 2 * ((l >> 4) & 1) + ((l & 3) >> 1)) * 16 + 8 * (l & 1);
+            v_addr[i] = rv * PITCH + (4 * i + 2 * ((l >> 4) & 1) + ((l & 3) >> 1)) * 16 + 8 * (l & 1);
     }
     const int n_chunks = (n_keys + kStripChunk - 1) / kStripChunk;
     constexpr int VDEPTH = 3;   // chunks in registers ahead of the one in LDS
@@ -237,7 +233,6 @@ __global__ __launch_bounds__(256) void slim_prefill_strip_kernel(const StripPara
         if (j < n_chunks) load_v(j, vst[j]);
     auto chunk = [&](int ch, u32x4 (&vreg)[NPV]) {
         store_v(vreg);
-        strip_lds_barrier();
         if (ch + VDEPTH < n_chunks) load_v(ch + VDEPTH, vreg);
         const int kb = ch * kStripChunk + kStripTile * tp;   // first key of this wave's tile
         if (kb < n_keys) {
@@ -247,21 +242,21 @@ __global__ __launch_bounds__(256) void slim_prefill_strip_kernel(const StripPara
                 const bf16x8 pb = *reinterpret_cast<const bf16x8*>(strip + l32 * SROW + (kb + 16 * ks + 8 * hh) * 2);
 #pragma unroll
                 for (int i = 0; i < DTW; ++i) {
-                    const char* va = stage + v_addr[i] + 16 * ks * ROWLV;
+                    const char* va = mine + v_addr[i] + 16 * ks * PITCH;
                     const s16x4 lo = lds_read_tr16(reinterpret_cast<const uint16_t*>(va));
-                    const s16x4 hi = lds_read_tr16(reinterpret_cast<const uint16_t*>(va + 4 * ROWLV));
+                    const s16x4 hi = lds_read_tr16(reinterpret_cast<const uint16_t*>(va + 4 * PITCH));
                     const s16x8 av = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
                     o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb, o[i], 0, 0, 0);
                 }
             }
         }
-        strip_lds_barrier();   // everyone is done with this chunk before the next one replaces it
     };
     for (int ch = 0; ch < n_chunks; ch += VDEPTH) {
 #pragma unroll
         for (int j = 0; j < VDEPTH; ++j)
             if (ch + j < n_chunks) chunk(ch + j, vst[j]);
     }
+    __syncthreads();   // every wave is done with the strip, whose place the merge below takes
 
     // ---- the two tile parities of each half are added (through the strip's place: the strip is dead), divided by
     // the row sum and stored.  Register r of tile i is d = 32 (DTW dh + i) + 8 (r/4) + 4 hh + r%4 of row my_q.
