@@ -5,19 +5,20 @@
 // variant of slim_prefill_kernel, which never holds more than a 32-key tile of a row block's scores.
 //
 // The buffer is LDS: 32 query rows x up to 2048 keys x 2 bytes = 128 KB of the compute unit's 160 KB, which is
-// what fixes the block at 32 rows.  One workgroup (4 waves, one per SIMD) owns a row block:
-//   pass 1  scores.  Wave w takes the 32-key tiles t = w, w + 4, ...: S^T = K Q^T on v_mfma_f32_32x32x16_bf16,
+// what fixes the block at 32 rows.  One workgroup (8 waves, two per SIMD) owns a row block:
+//   pass 1  scores.  Wave w takes the 32-key tiles t = w, w + 8, ...: S^T = K Q^T on v_mfma_f32_32x32x16_bf16,
 //           the K tile as A operand straight from global memory (lane = key, 16-byte pieces of its row), Q^T as B
 //           operand in registers.  Scaled to log2 units, masked, and written to the strip as fp16, each tile
 //           relative to a reference of its own (kept per tile and row in a small table); the row maxima are kept
 //           on the way (in-lane, then across the wave's halves, then across the waves).
 //   pass 2  softmax over the strip, in place: p = exp2(u - max) in fp32, summed in fp32, rounded to bf16 over
-//           the fp16 score it came from.  Pure vector work, all 256 threads.
-//   pass 3  strip times V.  Wave w takes tile (w & 1) of every 64-key chunk and half (w >> 1) of the head
-//           dimension, and brings in just that piece of V itself (128-bit loads, three chunks ahead in registers,
-//           an LDS region of its own, so no barriers): O^T += V^T P^T with P^T read from the strip as it stands
-//           (B operand: lane = query, 8 consecutive keys) and V^T through the LDS transpose read.  The two tile
-//           parities of a half are added at the end, divided by the row sum and stored.
+//           the fp16 score it came from.  Pure vector work, all 512 threads.
+//   pass 3  strip times V.  A wave takes one 32-column slice of the head dimension and one tile position of every
+//           chunk (D = 128: 4 slices x 2 tiles of a 64-key chunk; D = 64: 2 slices x 4 tiles of a 128-key chunk),
+//           and brings in just that piece of V itself (128-bit loads, three chunks ahead in registers, an LDS
+//           region of its own, so no barriers): O^T += V^T P^T with P^T read from the strip as it stands (B
+//           operand: lane = query, 8 consecutive keys) and V^T through the LDS transpose read.  The tile
+//           positions of a slice are added at the end, divided by the row sum and stored.
 // A score waits in the strip as the fp16 of u - ref, ref being the wave's row maximum up to and including the
 // score's own tile: never positive, small exactly where the probability is not, so the 11 significant bits cost
 // less than 2^-11 of log2(1/p) in the exponent (at most 0.4 % of a probability near 2^-8, less above and nothing
@@ -30,7 +31,7 @@ namespace slim {
 
 constexpr int kStripRows = 32;     // query rows per row block
 constexpr int kStripTile = 32;     // keys per score tile
-constexpr int kStripChunk = 64;    // keys per staged V chunk
+constexpr int kStripWaves = 8;     // waves per workgroup
 constexpr float kStripClamp = 65000.0f;
 
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
@@ -52,24 +53,28 @@ __device__ __forceinline__ float strip_dpp(float v) {
 
 // NC: key columns the strip has room for (the sequence length rounded up, one of a few size classes)
 template <int D, int NC, bool OUT_F32>
-__global__ __launch_bounds__(256) void slim_prefill_strip_kernel(const StripParams p) {
+__global__ __launch_bounds__(64 * kStripWaves) void slim_prefill_strip_kernel(const StripParams p) {
+    constexpr int NW = kStripWaves;
     constexpr int KS = D / 16;          // k-steps of a score tile
-    constexpr int DT = D / 32;          // 32-row tiles of O^T
-    constexpr int DTW = DT / 2;         // of which a wave takes half
+    constexpr int DT = D / 32;          // 32-column slices of the head dimension (32-row tiles of O^T): a wave takes one
+    constexpr int NTP = NW / DT;        // tile positions of a V chunk: the waves that share a slice
+    constexpr int CHUNK = kStripTile * NTP;   // keys per V chunk
+    static_assert(NW % DT == 0, "slices times tile positions = waves");
     constexpr int ROWB = 2 * D;         // bytes per K/V row in memory
     constexpr int SROW = 2 * NC + 16;   // strip row pitch: the padding shifts every row by 16 bytes, so the 128-bit reads of 16 rows meet 16 different bank groups
     constexpr int STRIP_BYTES = kStripRows * SROW;
-    constexpr int STAGE_BYTES = 4 * kStripTile * (D + 32);   // V staging: a region of 32 half rows (padded) per wave
+    constexpr int PITCH = 64 + 16;      // staged V row pitch: a 32-column slice of a row, padded
+    constexpr int STAGE_BYTES = NW * kStripTile * PITCH;   // V staging: a region of 32 row slices per wave
     constexpr int REF_BYTES = (NC / kStripTile) * 32 * 4;   // one reference per tile and row
-    static_assert(NC % kStripChunk == 0, "the strip holds whole chunks");
-    static_assert(STRIP_BYTES >= 2 * DTW * 16 * 64 * 4, "the partial outputs are merged in the strip's place");
+    static_assert(NC % CHUNK == 0, "the strip holds whole chunks");
+    static_assert(STRIP_BYTES >= NW * 4 * 64 * 16, "the partial outputs are merged in the strip's place");
 
-    __shared__ __attribute__((aligned(16))) char smem[STRIP_BYTES + STAGE_BYTES + REF_BYTES + (4 * 32 + 32 + 32) * 4];
+    __shared__ __attribute__((aligned(16))) char smem[STRIP_BYTES + STAGE_BYTES + REF_BYTES + (NW * 32 + 32 + 32) * 4];
     char* const strip = smem;
     char* const stage = smem + STRIP_BYTES;
     float* const refS = reinterpret_cast<float*>(stage + STAGE_BYTES);   // [tile][32 rows] what a tile's scores are relative to
-    float* const mS = refS + (NC / kStripTile) * 32;                      // [4 waves][32 rows] maxima of pass 1
-    float* const mrow = mS + 4 * 32;                                      // [32] the rows' maxima
+    float* const mS = refS + (NC / kStripTile) * 32;                      // [waves][32 rows] maxima of pass 1
+    float* const mrow = mS + NW * 32;                                     // [32] the rows' maxima
     float* const lrow = mrow + 32;                                        // [32] the rows' sums
 
     // workgroup -> (batch*head, row block); consecutive virtual ids (the row blocks of a head, which share K/V)
@@ -116,12 +121,12 @@ __global__ __launch_bounds__(256) void slim_prefill_strip_kernel(const StripPara
         for (int s = 0; s < KS; ++s) dst[s] = __builtin_amdgcn_raw_buffer_load_b128(krs, off + 32 * s, 0, 0);
     };
     float m = kMasked;   // this wave's running row maximum (log2 units), the same in both halves of the wave
-    // (one wave per SIMD and nothing else to hide the loads behind: three tiles' fragments are in flight per wave)
+    // (three tiles' fragments are in flight per wave)
     constexpr int KDEPTH = 3;
     u32x4 kf[KDEPTH][KS];
 #pragma unroll
     for (int j = 0; j < KDEPTH; ++j)
-        if (w + 4 * j < n_tiles) load_k(w + 4 * j, kf[j]);
+        if (w + NW * j < n_tiles) load_k(w + NW * j, kf[j]);
     auto score_tile = [&](int t, u32x4 (&kfr)[KS]) {
         f32x16 acc;
 #pragma unroll
@@ -129,7 +134,7 @@ __global__ __launch_bounds__(256) void slim_prefill_strip_kernel(const StripPara
 #pragma unroll
         for (int s = 0; s < KS; ++s)
             acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kfr[s]), qreg[s], acc, 0, 0, 0);
-        if (t + 4 * KDEPTH < n_tiles) load_k(t + 4 * KDEPTH, kfr);   // the registers are free again: the tile three turns ahead
+        if (t + NW * KDEPTH < n_tiles) load_k(t + NW * KDEPTH, kfr);   // the registers are free again: the tile three turns ahead
         // register r of this lane is key 32 t + 8 (r/4) + 4 hh + r%4 of query row my_q
         const int rel = lim - (t * kStripTile + 4 * hh);   // keys of this lane up to offset rel are visible
         float u[16];
@@ -149,22 +154,27 @@ __global__ __launch_bounds__(256) void slim_prefill_strip_kernel(const StripPara
             *reinterpret_cast<f16x4*>(strip + l32 * SROW + (t * kStripTile + 8 * r4 + 4 * hh) * 2) = hv;
         }
     };
-    for (int t = w; t < n_tiles; t += 4 * KDEPTH) {
+    for (int t = w; t < n_tiles; t += NW * KDEPTH) {
 #pragma unroll
         for (int j = 0; j < KDEPTH; ++j)
-            if (t + 4 * j < n_tiles) score_tile(t + 4 * j, kf[j]);
+            if (t + NW * j < n_tiles) score_tile(t + NW * j, kf[j]);
     }
     if (hh == 0) mS[w * 32 + l32] = m;   // (a wave without tiles leaves the stand-in for minus infinity)
     __syncthreads();
-    if (tid < 32) mrow[tid] = fmaxf(fmaxf(mS[tid], mS[32 + tid]), fmaxf(mS[64 + tid], mS[96 + tid]));
+    if (tid < 32) {
+        float mx = mS[tid];
+#pragma unroll
+        for (int ww = 1; ww < NW; ++ww) mx = fmaxf(mx, mS[ww * 32 + tid]);
+        mrow[tid] = mx;
+    }
     __syncthreads();
 
-    // ---- pass 2: softmax over the strip, in place.  Thread = (row tid / 8, 8-key groups tid % 8, +8, ...).
+    // ---- pass 2: softmax over the strip, in place.  Thread = (row tid / 16, 8-key groups tid % 16, +16, ...).
     {
-        const int row = tid >> 3;
+        const int row = tid >> 4;
         const float mr = mrow[row];
         float sum = 0.0f;
-        for (int j = (tid & 7) * 8; j < n_keys; j += 64) {
+        for (int j = (tid & 15) * 8; j < n_keys; j += 128) {
             char* at = strip + row * SROW + j * 2;
             const f16x8 u8 = *reinterpret_cast<const f16x8*>(at);
             const float shift = refS[(j / kStripTile) * 32 + row] - mr;   // the tile's reference against the row's maximum
@@ -181,51 +191,40 @@ __global__ __launch_bounds__(256) void slim_prefill_strip_kernel(const StripPara
         }
         sum += strip_dpp<0xB1>(sum);    // quad_perm [1,0,3,2]
         sum += strip_dpp<0x4E>(sum);    // quad_perm [2,3,0,1]
-        sum += strip_dpp<0x141>(sum);   // row_half_mirror: the other quad of the row's 8 threads
-        if ((tid & 7) == 0) lrow[row] = sum;
+        sum += strip_dpp<0x141>(sum);   // row_half_mirror: the other quad of the eight
+        sum += strip_dpp<0x140>(sum);   // row_mirror: the other eight of the row's 16 threads
+        if ((tid & 15) == 0) lrow[row] = sum;
     }
     __syncthreads();
 
-    // ---- pass 3: strip times V.  Wave (tp, dh) needs, of every 64-key chunk, the 32 keys of its tile parity and the
-    // half of the head dimension it accumulates: it loads exactly that piece (8 or 4 lanes per row, half a row each),
-    // stages it in an LDS region of its own and reads it back through the transpose read.  No other wave touches the
-    // region and LDS runs a wave's accesses in order, so the pass needs no barrier at all.
-    const int tp = w & 1, dh = w >> 1;
-    constexpr int ROWW = D;                              // bytes of a V row a wave takes: half the head dimension
-    constexpr int LPRW = ROWW / 16;                      // lanes per row
-    constexpr int NPV = kStripTile * LPRW / 64;          // 128-bit loads per lane and chunk
-    constexpr int PITCH = ROWW + 32;                     // staged row pitch (spreads the transpose reads over the banks)
-    static_assert(4 * kStripTile * PITCH <= STAGE_BYTES, "the four waves' regions fit the staging buffer");
+    // ---- pass 3: strip times V.  Wave (tpos, dq) needs, of every chunk, the 32 keys at its tile position and its
+    // 32-column slice of the head dimension: it loads exactly that piece (4 lanes per row, 64 bytes of it), stages it
+    // in an LDS region of its own and reads it back through the transpose read.  No other wave touches the region
+    // and LDS runs a wave's accesses in order, so the pass needs no barrier at all.
+    const int tpos = w % NTP, dq = w / NTP;
+    constexpr int NPV = 2;                               // 128-bit loads per lane and chunk: 16 rows each
     char* const mine = stage + w * (kStripTile * PITCH);
     auto load_v = [&](int ch, u32x4 (&dst)[NPV]) {
 #pragma unroll
         for (int i = 0; i < NPV; ++i) {
-            const int row = (64 / LPRW) * i + l / LPRW, col = l % LPRW;
-            dst[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (ch * kStripChunk + kStripTile * tp + row) * ROWB + ROWW * dh + col * 16, 0, 0);
+            const int row = 16 * i + l / 4, col = l % 4;
+            dst[i] = __builtin_amdgcn_raw_buffer_load_b128(vrs, (ch * CHUNK + kStripTile * tpos + row) * ROWB + 64 * dq + col * 16, 0, 0);
         }
     };
     auto store_v = [&](const u32x4 (&src)[NPV]) {
 #pragma unroll
         for (int i = 0; i < NPV; ++i) {
-            const int row = (64 / LPRW) * i + l / LPRW, col = l % LPRW;
+            const int row = 16 * i + l / 4, col = l % 4;
             *reinterpret_cast<u32x4*>(mine + row * PITCH + col * 16) = src[i];
         }
     };
-    f32x16 o[DTW];
+    f32x16 o;
 #pragma unroll
-    for (int i = 0; i < DTW; ++i)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o[i][r] = 0.0f;
+    for (int r = 0; r < 16; ++r) o[r] = 0.0f;
     // V^T A operand of 16 keys x 32 columns: the 16 lanes of a group fetch 4 rows (4 lanes per row, 8 bytes each)
     // and lane i of the group receives column i of those rows; this lane's rows are 8 hh + [0,4) and + 4.
-    int v_addr[DTW];
-    {
-        const int rv = 8 * hh + ((l & 15) >> 2);
-#pragma unroll
-        for (int i = 0; i < DTW; ++i)
-            v_addr[i] = rv * PITCH + (4 * i + 2 * ((l >> 4) & 1) + ((l & 3) >> 1)) * 16 + 8 * (l & 1);
-    }
-    const int n_chunks = (n_keys + kStripChunk - 1) / kStripChunk;
+    const int v_addr = (8 * hh + ((l & 15) >> 2)) * PITCH + (2 * ((l >> 4) & 1) + ((l & 3) >> 1)) * 16 + 8 * (l & 1);
+    const int n_chunks = (n_keys + CHUNK - 1) / CHUNK;
     constexpr int VDEPTH = 3;   // chunks in registers ahead of the one in LDS
     u32x4 vst[VDEPTH][NPV];
 #pragma unroll
@@ -234,20 +233,17 @@ __global__ __launch_bounds__(256) void slim_prefill_strip_kernel(const StripPara
     auto chunk = [&](int ch, u32x4 (&vreg)[NPV]) {
         store_v(vreg);
         if (ch + VDEPTH < n_chunks) load_v(ch + VDEPTH, vreg);
-        const int kb = ch * kStripChunk + kStripTile * tp;   // first key of this wave's tile
+        const int kb = ch * CHUNK + kStripTile * tpos;   // first key of this wave's tile
         if (kb < n_keys) {
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
                 // P^T B operand: lane = query row l32, keys kb + 16 ks + 8 hh + [0,8)
                 const bf16x8 pb = *reinterpret_cast<const bf16x8*>(strip + l32 * SROW + (kb + 16 * ks + 8 * hh) * 2);
-#pragma unroll
-                for (int i = 0; i < DTW; ++i) {
-                    const char* va = mine + v_addr[i] + 16 * ks * PITCH;
-                    const s16x4 lo = lds_read_tr16(reinterpret_cast<const uint16_t*>(va));
-                    const s16x4 hi = lds_read_tr16(reinterpret_cast<const uint16_t*>(va + 4 * PITCH));
-                    const s16x8 av = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-                    o[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb, o[i], 0, 0, 0);
-                }
+                const char* va = mine + v_addr + 16 * ks * PITCH;
+                const s16x4 lo = lds_read_tr16(reinterpret_cast<const uint16_t*>(va));
+                const s16x4 hi = lds_read_tr16(reinterpret_cast<const uint16_t*>(va + 4 * PITCH));
+                const s16x8 av = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                o = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), pb, o, 0, 0, 0);
             }
         }
     };
@@ -258,49 +254,50 @@ __global__ __launch_bounds__(256) void slim_prefill_strip_kernel(const StripPara
     }
     __syncthreads();   // every wave is done with the strip, whose place the merge below takes
 
-    // ---- the two tile parities of each half are added (through the strip's place: the strip is dead), divided by
-    // the row sum and stored.  Register r of tile i is d = 32 (DTW dh + i) + 8 (r/4) + 4 hh + r%4 of row my_q.
-    f32x4* const mg = reinterpret_cast<f32x4*>(smem);   // [dh][i][r4][lane]
-    if (tp == 1) {
+    // ---- the tile positions of each slice are added (through the strip's place: the strip is dead), divided by
+    // the row sum and stored.  Register r is d = 32 dq + 8 (r/4) + 4 hh + r%4 of row my_q.
+    f32x4* const mg = reinterpret_cast<f32x4*>(smem);   // [wave][r4][lane]
+    if (tpos != 0) {
 #pragma unroll
-        for (int i = 0; i < DTW; ++i)
-#pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-                const f32x4 vsend = {o[i][4 * r4], o[i][4 * r4 + 1], o[i][4 * r4 + 2], o[i][4 * r4 + 3]};
-                mg[((dh * DTW + i) * 4 + r4) * 64 + l] = vsend;
-            }
+        for (int r4 = 0; r4 < 4; ++r4) {
+            const f32x4 vsend = {o[4 * r4], o[4 * r4 + 1], o[4 * r4 + 2], o[4 * r4 + 3]};
+            mg[(w * 4 + r4) * 64 + l] = vsend;
+        }
     }
     __syncthreads();
-    if (tp == 0 && my_q < S) {
+    if (tpos == 0 && my_q < S) {
         const float inv = 1.0f / lrow[l32];
         const long orow = (((long)b * p.Hq + h) * S + my_q) * (long)D;
 #pragma unroll
-        for (int i = 0; i < DTW; ++i)
+        for (int r4 = 0; r4 < 4; ++r4) {
+            float xo[4] = {o[4 * r4], o[4 * r4 + 1], o[4 * r4 + 2], o[4 * r4 + 3]};
 #pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-                const f32x4 ot = mg[((dh * DTW + i) * 4 + r4) * 64 + l];
-                float xo[4];
+            for (int t2 = 1; t2 < NTP; ++t2) {   // in the order of the tile positions
+                const f32x4 ot = mg[((w + t2) * 4 + r4) * 64 + l];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) xo[e] = (o[i][4 * r4 + e] + ot[e]) * inv;
-                const int d = 32 * (DTW * dh + i) + 8 * r4 + 4 * hh;
-                if (OUT_F32) {
-                    const f32x4 ov = {xo[0], xo[1], xo[2], xo[3]};
-                    *reinterpret_cast<f32x4*>((float*)p.out + orow + d) = ov;
-                } else {
-                    u32x2 ov;
-                    ov[0] = pack_bf16x2(xo[0], xo[1]);
-                    ov[1] = pack_bf16x2(xo[2], xo[3]);
-                    *reinterpret_cast<u32x2*>((uint16_t*)p.out + orow + d) = ov;
-                }
+                for (int e = 0; e < 4; ++e) xo[e] += ot[e];
             }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) xo[e] *= inv;
+            const int d = 32 * dq + 8 * r4 + 4 * hh;
+            if (OUT_F32) {
+                const f32x4 ov = {xo[0], xo[1], xo[2], xo[3]};
+                *reinterpret_cast<f32x4*>((float*)p.out + orow + d) = ov;
+            } else {
+                u32x2 ov;
+                ov[0] = pack_bf16x2(xo[0], xo[1]);
+                ov[1] = pack_bf16x2(xo[2], xo[3]);
+                *reinterpret_cast<u32x2*>((uint16_t*)p.out + orow + d) = ov;
+            }
+        }
     }
 }
 
 template <int D, int NC>
 static hipError_t launch_strip_nc(const StripParams& p, bool out_f32, hipStream_t stream) {
     const unsigned grid = (unsigned)(8 * p.chunk);
-    if (out_f32) hipLaunchKernelGGL((slim_prefill_strip_kernel<D, NC, true>), dim3(grid), dim3(256), 0, stream, p);
-    else hipLaunchKernelGGL((slim_prefill_strip_kernel<D, NC, false>), dim3(grid), dim3(256), 0, stream, p);
+    if (out_f32) hipLaunchKernelGGL((slim_prefill_strip_kernel<D, NC, true>), dim3(grid), dim3(64 * kStripWaves), 0, stream, p);
+    else hipLaunchKernelGGL((slim_prefill_strip_kernel<D, NC, false>), dim3(grid), dim3(64 * kStripWaves), 0, stream, p);
     return hipGetLastError();
 }
 
