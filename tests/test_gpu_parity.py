@@ -572,6 +572,53 @@ def test_calls_follow_the_current_stream(sa, oracle):
         assert torch.equal(a, b)
 
 
+def test_calls_on_two_streams_at_once_do_not_disturb_each_other(sa, oracle):
+    # the library keeps no state between calls (the static-scratch decode aside): two different chains of calls,
+    # each with buffers of its own, enqueued alternately on two streams with nothing to order them, give bit for bit
+    # what each gives alone
+    rng = np.random.default_rng(96)
+    scale = 1.0 / math.sqrt(128)
+    shapes = [(1, 8, 2, 700, 128), (2, 4, 4, 333, 128)]
+    data = []
+    for B, Hq, Hkv, S, D in shapes:
+        q, k, v = (dev_bf16(normal_bf16(rng, shp)) for shp in ((B, Hq, S, D), (B, Hkv, S, D), (B, Hkv, S, D)))
+        ws = torch.empty((sa.slim_attn_decode_int8_workspace_bytes(B, Hq, Hkv, S, D),), dtype=torch.uint8, device="cuda")
+        data.append((q, k, v, q[:, :, S - 1:S].contiguous(), ws))
+
+    def links(q, k, v, q1, ws):
+        # one chain, cut into its calls, so that the two chains can be dealt out alternately
+        box = {}
+        yield lambda: box.update(zip(("kc", "ks", "vc", "vs"), sa.kv_quant_int8_pair(k, v)))
+        yield lambda: box.update(pre=sa.slim_attn_prefill(q, k, v, scale, True))
+        yield lambda: box.update(pre8=sa.slim_attn_prefill(q, box["kc"], box["vc"], scale, True, k_scale=box["ks"], v_scale=box["vs"]))
+        yield lambda: box.update(dec=sa.slim_attn_decode_int8(q1, box["kc"], box["ks"], box["vc"], box["vs"], scale, workspace=ws))
+        yield lambda: box.update(strip=sa.slim_attn_prefill_strip(q, k, v, scale, True))
+        yield box
+
+    def run_alone(d):
+        *calls, box = list(links(*d))
+        for c in calls:
+            c()
+        torch.cuda.synchronize()
+        return box
+
+    refs = [run_alone(d) for d in data]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for st in streams:
+        st.wait_stream(torch.cuda.current_stream())
+    chains = [list(links(*d)) for d in data]
+    for step_i in range(len(chains[0]) - 1):
+        for st, ch in zip(streams, chains):
+            with torch.cuda.stream(st):
+                ch[step_i]()
+    for st in streams:
+        st.synchronize()
+    for ref, ch in zip(refs, chains):
+        got = ch[-1]
+        for name in ref:
+            assert torch.equal(got[name].view(torch.uint8), ref[name].view(torch.uint8)), name + " differs when two streams run at once"
+
+
 def test_every_entry_point_replays_from_a_hip_graph(sa, oracle):
     # no entry point allocates, synchronises or clears memory with a memset node: a whole serving step (build the
     # cache, prefill over it, the comparison variants, append a token, decode) recorded into one HIP graph gives, on
