@@ -102,7 +102,16 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
     auto swz_k = [](int r) { return KV_I8 ? 0 : (r / RPL) & (CPL - 1); };
     auto swz_v = [](int r) { return KV_I8 ? 0 : ((r / RPL) & (CPL / 4 - 1)) << 2; };
 
-    __shared__ __attribute__((aligned(16))) char smem[RING_BYTES + kRingK * 2 * kBC * 4];
+    // The row block's Q: 128 unpadded rows, the 16-byte chunk c of row r at chunk position c ^ qswz(r) (the bf16 K tile's layout)
+    constexpr int ROWQ = 2 * D;                // bytes per Q row, in memory and in LDS
+    constexpr int CPQ = ROWQ / 16;             // 16-byte chunks per row: 16 or 8
+    constexpr int RPQ = 64 / CPQ;              // rows per wave-wide load: 4 or 8
+    constexpr int NQ = kBR / 8 / RPQ;          // loads per wave and row block (a wave brings in 16 rows): 4 or 2
+    constexpr int Q_OFF = RING_BYTES + kRingK * 2 * kBC * 4;
+    auto qswz = [](int r) { return (r / (256 / ROWQ)) & (CPQ - 1); };
+
+    constexpr bool Q_LDS = !KV_I8;             // (the INT8 kernel keeps plain loads into the registers: measured faster there)
+    __shared__ __attribute__((aligned(16))) char smem[Q_OFF + (Q_LDS ? kBR * ROWQ : 0)];
     float* const scS = reinterpret_cast<float*>(smem + RING_BYTES);   // INT8: per slot [0,32) k_scale*c, [32,64) v_scale
 
     // workgroup -> (batch*head, row-block pair).  Hardware deals workgroup ids round-robin over the 8
@@ -125,16 +134,50 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
     const int l = tid & 63, l32 = l & 31, hh = l >> 5;
     const long kvrow0 = ((long)b * p.Hkv + g) * (long)S;
 
-    // Q^T B-operands of a row block: lane holds row my_q, d = 16 s + 8 hh + [0,8).  The first row block's are
-    // requested here, ahead of the address tables below: they come from cold memory.
+    // Q^T B-operands of a row block: lane holds row my_q, d = 16 s + 8 hh + [0,8).  With bf16 K/V the 128 rows come
+    // in through LDS, by buffer loads with an LDS destination that move 64 consecutive 16-byte pieces each: loads
+    // that give every lane a row of its own are taken lane by lane by the memory pipe (about 4 k cycles per row block
+    // for the eight waves' fragments, with the first K and V tiles waiting behind them, against about 0.7 k this
+    // way); rows past the end of the sequence arrive as zeros.  The INT8 kernel loads its fragments straight into
+    // the registers.  The first row block's are requested here, ahead of the address tables below: they come from
+    // cold memory.
     bf16x8 qreg[KS];
-    auto load_q = [&](int rb_q) {
-        const int q_row = min(rb_q * kBR + 32 * w + l32, S - 1);
-        const uint16_t* qp = p.q + (((long)b * p.Hq + h) * S + q_row) * (long)D + 8 * hh;
+    const unsigned smem_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
+    u32x4 qrs_raw;
+    {
+        const unsigned long long a64 = (unsigned long long)(p.q + ((long)b * p.Hq + h) * (long)S * D);
+        qrs_raw[0] = __builtin_amdgcn_readfirstlane((unsigned)a64);
+        qrs_raw[1] = __builtin_amdgcn_readfirstlane((unsigned)(a64 >> 32) & 0xffffu);
+        qrs_raw[2] = __builtin_amdgcn_readfirstlane((unsigned)S * ROWQ);
+        qrs_raw[3] = 0x00020000u;
+    }
+    auto request_q = [&](int rb_q) {
+        if constexpr (!Q_LDS) {
+            const int q_row = min(rb_q * kBR + 32 * w + l32, S - 1);
+            const uint16_t* qp = p.q + (((long)b * p.Hq + h) * S + q_row) * (long)D + 8 * hh;
 #pragma unroll
-        for (int s = 0; s < KS; ++s) qreg[s] = *reinterpret_cast<const bf16x8*>(qp + 16 * s);
+            for (int s = 0; s < KS; ++s) qreg[s] = *reinterpret_cast<const bf16x8*>(qp + 16 * s);
+            return;
+        }
+#pragma unroll
+        for (int j = 0; j < NQ; ++j) {
+            const int r = 16 * w8 + RPQ * j + l / CPQ, pos = l % CPQ;   // row of the block, chunk position in LDS
+            const unsigned voff = (unsigned)(rb_q * kBR + r) * ROWQ + (unsigned)((pos ^ qswz(r)) * 16);
+            const unsigned dst = __builtin_amdgcn_readfirstlane(smem_base + (unsigned)(Q_OFF + (16 * w8 + RPQ * j) * ROWQ));
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, 0 offen lds"
+                         :
+                         : "s"(dst), "v"(voff), "s"(qrs_raw)
+                         : "memory", "m0");
+        }
     };
-    load_q(x);
+    // this wave's fragments of the Q in LDS (once the requests have landed and a barrier has passed)
+    auto read_q = [&]() {
+        if constexpr (!Q_LDS) return;
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+            qreg[s] = *reinterpret_cast<const bf16x8*>(smem + Q_OFF + (32 * w + l32) * ROWQ + (((2 * s + hh) ^ qswz(l32)) * 16));
+    };
+    request_q(x);
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- staging.  The buffer descriptors cover exactly this head's K (V) slab: pieces past the end of
@@ -169,7 +212,6 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         d_koff[j] = (unsigned)r * ROWB + (unsigned)((pos ^ swz_k(r)) * 16);
         d_voff[j] = (unsigned)r * ROWB + (unsigned)((pos ^ swz_v(r)) * 16);
     }
-    const unsigned smem_base = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
     auto dma_tile = [&](const u32x4 rs, const unsigned (&off)[NLD], int t, int lds_off, bool wanted = true) {
         // (a tile that is not wanted is requested past the end of the slab: zeros arrive, no memory is read)
         const unsigned tbase = wanted ? (unsigned)t * (kBC * ROWB) : (unsigned)S * ROWB;
@@ -351,6 +393,7 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
             }
         }
         __syncthreads();
+        read_q();
 
         // Operand fragments, read from LDS one matrix phase ahead:
         //   kfr: K tile as A operand, lane = key l32, d = 16 s + 8 hh + [0,8)
@@ -638,10 +681,10 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         }
         if constexpr (MODE == 1) {   // this sweep's result: the row maxima; nothing to merge, nothing to store
             if (hh == 0 && my_q < S) p.row_max[((((long)b * p.Hq + h) * S + my_q) * 2) + grp] = M;
-            if (has_next) load_q(p.n_rb - 1 - x);
+            if (has_next) request_q(p.n_rb - 1 - x);
             continue;
         }
-        if (has_next) load_q(p.n_rb - 1 - x);   // in flight during the merge
+        if (has_next) request_q(p.n_rb - 1 - x);   // in flight during the merge (every wave read its fragments of this block's Q long ago)
 
         // ---- merge the two groups' partial results.  A wave keeps half of its O^T tiles and hands the
         // other half, with its max and row sum, to its partner (same rows, other group) through LDS.

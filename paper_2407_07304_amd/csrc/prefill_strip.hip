@@ -107,12 +107,24 @@ __global__ __launch_bounds__(64 * kStripWaves) void slim_prefill_strip_kernel(co
     const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc((void*)(p.k + kvrow0 * D), 0, (int)((unsigned)S * ROWB), 0x00020000);
     const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc((void*)(p.v + kvrow0 * D), 0, (int)((unsigned)S * ROWB), 0x00020000);
 
-    // ---- pass 1: the score strip.  Q^T B operands: lane holds row my_q, d = 16 s + 8 hh + [0,8).
+    // ---- pass 1: the score strip.  Q^T B operands: lane holds row my_q, d = 16 s + 8 hh + [0,8); the same for every
+    // wave.  The block's 32 rows are loaded once, 64 consecutive 16-byte pieces per instruction, into the V staging
+    // buffer (idle until pass 3) and every wave reads its fragments from there: eight waves each loading a row per
+    // lane would keep the memory pipe busy lane by lane for some four thousand cycles per workgroup.
     bf16x8 qreg[KS];
     {
-        const uint16_t* qp = p.q + (((long)b * p.Hq + h) * S + min(my_q, S - 1)) * (long)D + 8 * hh;
+        constexpr int CPQ = ROWB / 16;              // 16-byte pieces per Q row
+        constexpr int QPITCH = ROWB + 16;           // staged row pitch: 16 rows' 128-bit reads meet 16 different bank groups
+        static_assert(kStripRows * QPITCH <= STAGE_BYTES, "the Q rows fit the staging buffer");
+        const __amdgpu_buffer_rsrc_t qrs = __builtin_amdgcn_make_buffer_rsrc((void*)(p.q + ((long)b * p.Hq + h) * (long)S * D), 0, (int)((unsigned)S * ROWB), 0x00020000);
+        for (int pid = tid; pid < kStripRows * CPQ; pid += 64 * NW) {
+            const int row = pid / CPQ, col = pid % CPQ;   // (rows past the end of the sequence read as zero)
+            const u32x4 piece = __builtin_amdgcn_raw_buffer_load_b128(qrs, (i0 + row) * ROWB + col * 16, 0, 0);
+            *reinterpret_cast<u32x4*>(stage + row * QPITCH + col * 16) = piece;
+        }
+        __syncthreads();
 #pragma unroll
-        for (int s = 0; s < KS; ++s) qreg[s] = *reinterpret_cast<const bf16x8*>(qp + 16 * s);
+        for (int s = 0; s < KS; ++s) qreg[s] = *reinterpret_cast<const bf16x8*>(stage + l32 * QPITCH + 32 * s + 16 * hh);
     }
     // K fragment of k-step s of tile t: lane = key 32 t + l32, bytes 32 s + 16 hh + [0,16) of its row
     auto load_k = [&](int t, u32x4 (&dst)[KS]) {
