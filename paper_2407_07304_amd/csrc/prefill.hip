@@ -688,18 +688,21 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
 
         // ---- merge the two groups' partial results.  A wave keeps half of its O^T tiles and hands the
         // other half, with its max and row sum, to its partner (same rows, other group) through LDS.
-        {
+        // The row block's output then goes out through LDS as well: a lane holds a few values of a row of its own,
+        // and stores of that shape (64 lanes, 32 rows, 8 or 16 bytes each) are taken lane by lane by the memory
+        // pipe and land as partial lines.  The tile is put together in the merge records' place (once every wave
+        // has read its partner's) and leaves as whole rows, 64 consecutive 16-byte pieces per instruction.
+        auto finish = [&](auto grp_c) {
+            constexpr int G = decltype(grp_c)::value;
+            constexpr int HALF = DT / 2;
+            constexpr int keep0 = G == 0 ? 0 : HALF, send0 = G == 0 ? HALF : 0;
             f32x4* mg = reinterpret_cast<f32x4*>(smem);   // [wave][NV][lane]; the ring is dead and quiet after the last barrier
             const float L = half_sum(lsum);
-            constexpr int HALF = DT / 2;
-            const int keep0 = grp == 0 ? 0 : HALF;
 #pragma unroll
             for (int dt = 0; dt < HALF; ++dt)
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
-                    f32x4 vsend;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) vsend[e] = grp == 0 ? o[HALF + dt][4 * r4 + e] : o[dt][4 * r4 + e];
+                    const f32x4 vsend = {o[send0 + dt][4 * r4], o[send0 + dt][4 * r4 + 1], o[send0 + dt][4 * r4 + 2], o[send0 + dt][4 * r4 + 3]};
                     mg[(w8 * NV + dt * 4 + r4) * 64 + l] = vsend;
                 }
             {
@@ -713,33 +716,73 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
             const float a_me = fast_exp2(M - m_all), a_ot = fast_exp2(oml[0] - m_all);
             const float inv = 1.0f / (L * a_me + oml[1] * a_ot);
             const float s_me = a_me * inv, s_ot = a_ot * inv;
-            const long orow = (((long)b * p.Hq + h) * S + my_q) * (long)D;
 #pragma unroll
             for (int dt = 0; dt < HALF; ++dt)
 #pragma unroll
                 for (int r4 = 0; r4 < 4; ++r4) {
                     const f32x4 ot = mg[(pw8 * NV + dt * 4 + r4) * 64 + l];
-                    float xo[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float mine = grp == 0 ? o[dt][4 * r4 + e] : o[HALF + dt][4 * r4 + e];
-                        xo[e] = fmaf(mine, s_me, ot[e] * s_ot);
-                    }
+                    for (int e = 0; e < 4; ++e) o[keep0 + dt][4 * r4 + e] = fmaf(o[keep0 + dt][4 * r4 + e], s_me, ot[e] * s_ot);
+                }
+            constexpr int OB = OUT_F32 ? 4 * D : 2 * D;   // bytes per output row
+            if constexpr (KV_I8) {
+                // (the INT8 kernel stores from the registers: the tile's extra live values cost it more, through the
+                // register allocation of its prologue, than the stores save: measured)
+                if (my_q < S) {
+                    char* const orow = (char*)p.out + (((long)b * p.Hq + h) * S + my_q) * (long)OB;
+#pragma unroll
+                    for (int dt = 0; dt < HALF; ++dt)
+#pragma unroll
+                        for (int r4 = 0; r4 < 4; ++r4) {
+                            const int d = 32 * (keep0 + dt) + 8 * r4 + 4 * hh;
+                            const f32x16& ok = o[keep0 + dt];
+                            if (OUT_F32) {
+                                const f32x4 ov = {ok[4 * r4], ok[4 * r4 + 1], ok[4 * r4 + 2], ok[4 * r4 + 3]};
+                                *reinterpret_cast<f32x4*>(orow + 4 * d) = ov;
+                            } else {
+                                u32x2 ov;
+                                ov[0] = pack_bf16x2(ok[4 * r4], ok[4 * r4 + 1]);
+                                ov[1] = pack_bf16x2(ok[4 * r4 + 2], ok[4 * r4 + 3]);
+                                *reinterpret_cast<u32x2*>(orow + 2 * d) = ov;
+                            }
+                        }
+                }
+                return;
+            }
+            constexpr int OPITCH = OB + 16;               // tile row pitch: spreads the column-wise writes over the banks
+            static_assert(kBR * OPITCH <= RING_BYTES, "the output tile fits where the ring was");
+            __syncthreads();
+#pragma unroll
+            for (int dt = 0; dt < HALF; ++dt)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
                     // register r of tile dt is d = 32 dt + 8 (r/4) + 4 hh + r%4
                     const int d = 32 * (keep0 + dt) + 8 * r4 + 4 * hh;
-                    if (my_q < S) {
-                        if (OUT_F32) {
-                            f32x4 ov = {xo[0], xo[1], xo[2], xo[3]};
-                            *reinterpret_cast<f32x4*>((float*)p.out + orow + d) = ov;
-                        } else {
-                            u32x2 ov;
-                            ov[0] = pack_bf16x2(xo[0], xo[1]);
-                            ov[1] = pack_bf16x2(xo[2], xo[3]);
-                            *reinterpret_cast<u32x2*>((uint16_t*)p.out + orow + d) = ov;
-                        }
+                    char* at = smem + (32 * w + l32) * OPITCH;
+                    const f32x16& ok = o[keep0 + dt];
+                    if (OUT_F32) {
+                        const f32x4 ov = {ok[4 * r4], ok[4 * r4 + 1], ok[4 * r4 + 2], ok[4 * r4 + 3]};
+                        *reinterpret_cast<f32x4*>(at + 4 * d) = ov;
+                    } else {
+                        u32x2 ov;
+                        ov[0] = pack_bf16x2(ok[4 * r4], ok[4 * r4 + 1]);
+                        ov[1] = pack_bf16x2(ok[4 * r4 + 2], ok[4 * r4 + 3]);
+                        *reinterpret_cast<u32x2*>(at + 2 * d) = ov;
                     }
                 }
-        }
+            __syncthreads();
+            constexpr int PPR = OB / 16;                           // 16-byte pieces per row
+            constexpr int NST = kBR * PPR / kPrefillThreads;       // pieces per thread
+            char* const obase = (char*)p.out + (((long)b * p.Hq + h) * S + i0) * (long)OB;
+#pragma unroll
+            for (int i = 0; i < NST; ++i) {
+                const int pid = tid + kPrefillThreads * i, row = pid / PPR, col = pid % PPR;
+                const u32x4 piece = *reinterpret_cast<const u32x4*>(smem + row * OPITCH + col * 16);
+                if (i0 + row < S) *reinterpret_cast<u32x4*>(obase + (long)row * OB + col * 16) = piece;
+            }
+        };
+        if (grp == 0) finish(int_c<0>{});
+        else finish(int_c<1>{});
 
         // ---- the INT8 cache of this row block's own K and V rows, if asked for (section 2.2): the workgroup of
         // a KV head's first query head quantises them, 16 rows per wave, with the quantiser's row routine.
