@@ -277,9 +277,13 @@ __global__ __launch_bounds__(64 * kStripWaves) void slim_prefill_strip_kernel(co
         }
     }
     __syncthreads();
-    if (tpos == 0 && my_q < S) {
+    // The finished rows go out through the staging buffer (idle again) as whole rows, 64 consecutive 16-byte pieces
+    // per instruction: stores of a few values per lane and row are taken lane by lane by the memory pipe.
+    constexpr int OB = OUT_F32 ? 4 * D : 2 * D;   // bytes per output row
+    constexpr int OPITCH = OB + 16;
+    static_assert(kStripRows * OPITCH <= STAGE_BYTES, "the output tile fits the staging buffer");
+    if (tpos == 0) {
         const float inv = 1.0f / lrow[l32];
-        const long orow = (((long)b * p.Hq + h) * S + my_q) * (long)D;
 #pragma unroll
         for (int r4 = 0; r4 < 4; ++r4) {
             float xo[4] = {o[4 * r4], o[4 * r4 + 1], o[4 * r4 + 2], o[4 * r4 + 3]};
@@ -292,15 +296,26 @@ __global__ __launch_bounds__(64 * kStripWaves) void slim_prefill_strip_kernel(co
 #pragma unroll
             for (int e = 0; e < 4; ++e) xo[e] *= inv;
             const int d = 32 * dq + 8 * r4 + 4 * hh;
+            char* at = stage + l32 * OPITCH;
             if (OUT_F32) {
                 const f32x4 ov = {xo[0], xo[1], xo[2], xo[3]};
-                *reinterpret_cast<f32x4*>((float*)p.out + orow + d) = ov;
+                *reinterpret_cast<f32x4*>(at + 4 * d) = ov;
             } else {
                 u32x2 ov;
                 ov[0] = pack_bf16x2(xo[0], xo[1]);
                 ov[1] = pack_bf16x2(xo[2], xo[3]);
-                *reinterpret_cast<u32x2*>((uint16_t*)p.out + orow + d) = ov;
+                *reinterpret_cast<u32x2*>(at + 2 * d) = ov;
             }
+        }
+    }
+    __syncthreads();
+    {
+        constexpr int PPR = OB / 16;   // 16-byte pieces per row
+        char* const obase = (char*)p.out + (((long)b * p.Hq + h) * S + i0) * (long)OB;
+        for (int pid = tid; pid < kStripRows * PPR; pid += 64 * NW) {
+            const int row = pid / PPR, col = pid % PPR;
+            const u32x4 piece = *reinterpret_cast<const u32x4*>(stage + row * OPITCH + col * 16);
+            if (i0 + row < S) *reinterpret_cast<u32x4*>(obase + (long)row * OB + col * 16) = piece;
         }
     }
 }
