@@ -725,30 +725,6 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
                     for (int e = 0; e < 4; ++e) o[keep0 + dt][4 * r4 + e] = fmaf(o[keep0 + dt][4 * r4 + e], s_me, ot[e] * s_ot);
                 }
             constexpr int OB = OUT_F32 ? 4 * D : 2 * D;   // bytes per output row
-            if constexpr (KV_I8) {
-                // (the INT8 kernel stores from the registers: the tile's extra live values cost it more, through the
-                // register allocation of its prologue, than the stores save: measured)
-                if (my_q < S) {
-                    char* const orow = (char*)p.out + (((long)b * p.Hq + h) * S + my_q) * (long)OB;
-#pragma unroll
-                    for (int dt = 0; dt < HALF; ++dt)
-#pragma unroll
-                        for (int r4 = 0; r4 < 4; ++r4) {
-                            const int d = 32 * (keep0 + dt) + 8 * r4 + 4 * hh;
-                            const f32x16& ok = o[keep0 + dt];
-                            if (OUT_F32) {
-                                const f32x4 ov = {ok[4 * r4], ok[4 * r4 + 1], ok[4 * r4 + 2], ok[4 * r4 + 3]};
-                                *reinterpret_cast<f32x4*>(orow + 4 * d) = ov;
-                            } else {
-                                u32x2 ov;
-                                ov[0] = pack_bf16x2(ok[4 * r4], ok[4 * r4 + 1]);
-                                ov[1] = pack_bf16x2(ok[4 * r4 + 2], ok[4 * r4 + 3]);
-                                *reinterpret_cast<u32x2*>(orow + 2 * d) = ov;
-                            }
-                        }
-                }
-                return;
-            }
             constexpr int OPITCH = OB + 16;               // tile row pitch: spreads the column-wise writes over the banks
             static_assert(kBR * OPITCH <= RING_BYTES, "the output tile fits where the ring was");
             __syncthreads();
@@ -776,7 +752,9 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
             char* const obase = (char*)p.out + (((long)b * p.Hq + h) * S + i0) * (long)OB;
 #pragma unroll
             for (int i = 0; i < NST; ++i) {
-                const int pid = tid + kPrefillThreads * i, row = pid / PPR, col = pid % PPR;
+                // (the thread id, counted afresh: keeping it alive through the phase loops costs spills)
+                const int lane_now = (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u));
+                const int pid = (w8 * 64 + lane_now) + kPrefillThreads * i, row = pid / PPR, col = pid % PPR;
                 const u32x4 piece = *reinterpret_cast<const u32x4*>(smem + row * OPITCH + col * 16);
                 if (i0 + row < S) *reinterpret_cast<u32x4*>(obase + (long)row * OB + col * 16) = piece;
             }
