@@ -247,8 +247,13 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
     constexpr int NP = CH >= 256 ? CH / 256 : 1;
     const int gl = tid & 255;
     const bool has_p = CH >= 256 || w < CH / 64;
-    const bool has_s = KV_I8 && w == 3;   // lanes 0..31: k_scale of key l, lanes 32..63: v_scale of key l-32
-    const float* sslab = KV_I8 ? ((l < kBC ? p.ks : p.vs) + kvrow0) : nullptr;
+    // The tile's scales: the last wave of a group carries the 32 k_scales, the one before it the 32 v_scales (every
+    // choice here is uniform over the wave: a value that depends on the lane would have to live, as a register or as
+    // a spill, through the whole kernel).  Both halves of the wave load and store the same 32 values.
+    const bool has_s = KV_I8 && w >= 2;
+    const bool s_is_k = w == 3;
+    const float* const sbase = KV_I8 ? ((s_is_k ? p.ks : p.vs) + kvrow0) : nullptr;
+    const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc((void*)sbase, 0, KV_I8 ? (int)((unsigned)S * 4u) : 0, 0x00020000);
     unsigned p_off[NP];
     int p_kdst[NP][2], p_vdst[NP][2];
 #pragma unroll
@@ -261,16 +266,18 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
             p_vdst[i][e] = K_BYTES + row * ROWLV + (((2 * col + e) ^ swz_v(row)) * 16);
         }
     }
-    auto load_tile = [&](const __amdgpu_buffer_rsrc_t rs, int t, u32x4 (&dst)[NP]) {
+    auto load_tile_at = [&](const __amdgpu_buffer_rsrc_t rs, int t, u32x4 (&dst)[NP], const unsigned (&off)[NP]) {
         if (has_p) {
 #pragma unroll
             for (int i = 0; i < NP; ++i)
-                dst[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)((unsigned)t * (kBC * ROWB) + p_off[i]), 0, 0);
+                dst[i] = __builtin_amdgcn_raw_buffer_load_b128(rs, (int)((unsigned)t * (kBC * ROWB) + off[i]), 0, 0);
         }
     };
-    auto load_s = [&](int t, float& dst) {
-        if (has_s) dst = sslab[min(t * kBC + l32, S - 1)];
+    auto load_tile = [&](const __amdgpu_buffer_rsrc_t rs, int t, u32x4 (&dst)[NP]) { load_tile_at(rs, t, dst, p_off); };
+    auto load_s_at = [&](int t, float& dst, int lane32) {   // (a key past the end of the sequence gets scale 0: it is masked anyway)
+        if (has_s) dst = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(srs, (t * kBC + lane32) * 4, 0, 0));
     };
+    auto load_s = [&](int t, float& dst) { load_s_at(t, dst, l32); };
     auto store_tile = [&](int slot_off, const int (&dsts)[NP][2], const u32x4 (&src)[NP]) {   // 16 INT8 codes -> 16 bf16 (exact)
         if (has_p) {
 #pragma unroll
@@ -290,7 +297,7 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         }
     };
     auto store_s = [&](int slot, float s) {
-        if (has_s) scS[slot * (2 * kBC) + l] = l < kBC ? s * c : s;
+        if (has_s) scS[slot * (2 * kBC) + (s_is_k ? 0 : kBC) + l32] = s_is_k ? s * c : s;
     };
     struct Stage {
         u32x4 k[NP], v[NP];
@@ -335,10 +342,6 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         // earlier is staged here, all requests issued together.  Every V slot gets a tile (zeros past the
         // end of the sequence): whatever a skipped tile later leaves in place is finite data of this row
         // block, never the previous pass's merge buffer.
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o[dt][r] = 0.0f;
         if constexpr (MODE == 2) {   // the final maximum of this lane's row over this group's tiles
             M = p.row_max[((((long)b * p.Hq + h) * S + min(my_q, S - 1)) * 2) + grp];
         }
@@ -368,19 +371,31 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
             // each group stores in its first matrix phase (group 1 in phase 0: K 5, V 3; group 0 in phase 1: K 6, V 4)
             u32x4 ta[NP], tb[NP], tc[NP], td[NP], te[NP];
             float sa = 0.0f, sb = 0.0f, sc3 = 0.0f;
-            load_tile(krs, grp, ta);
-            load_tile(krs, 2 + grp, tb);
-            load_tile(vrs, grp, td);
-            load_s(grp, sa);
-            load_s(2 + grp, sb);
-            if (grp == 0) {
-                load_tile(krs, 4, tc);
-                load_tile(vrs, 2, te);
-                load_s(4, sc3);
+            // The addresses of these loads are put together here, from copies the compiler cannot see through: left
+            // to itself it computes all of them ahead of the pass loop, spills them, and reloads them one by one
+            // between the loads, and a reload is a memory access that waits, in order, for the tile loads before it
+            // (eight trips to cold memory one after the other instead of one).
+            unsigned off_now[NP];
+#pragma unroll
+            for (int i = 0; i < NP; ++i) {
+                off_now[i] = p_off[i];
+                asm volatile("" : "+v"(off_now[i]));
             }
-            load_tile(krs, 6 - grp, sg.k);
-            load_tile(vrs, 4 - grp, sg.v);
-            load_s(6 - grp, sg.s);
+            int l32_now = l32;
+            asm volatile("" : "+v"(l32_now));
+            load_tile_at(krs, grp, ta, off_now);
+            load_tile_at(krs, 2 + grp, tb, off_now);
+            load_tile_at(vrs, grp, td, off_now);
+            load_s_at(grp, sa, l32_now);
+            load_s_at(2 + grp, sb, l32_now);
+            if (grp == 0) {
+                load_tile_at(krs, 4, tc, off_now);
+                load_tile_at(vrs, 2, te, off_now);
+                load_s_at(4, sc3, l32_now);
+            }
+            load_tile_at(krs, 6 - grp, sg.k, off_now);
+            load_tile_at(vrs, 4 - grp, sg.v, off_now);
+            load_s_at(6 - grp, sg.s, l32_now);
             store_tile(grp * TILEBK, p_kdst, ta);
             store_tile((2 + grp) * TILEBK, p_kdst, tb);
             store_tile(grp * TILEBV, p_vdst, td);
@@ -394,6 +409,11 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         }
         __syncthreads();
         read_q();
+        // (the accumulators start here, not above: 64 registers the prologue's loads in flight can use)
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[dt][r] = 0.0f;
 
         // Operand fragments, read from LDS one matrix phase ahead:
         //   kfr: K tile as A operand, lane = key l32, d = 16 s + 8 hh + [0,8)
