@@ -274,10 +274,10 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
         }
     };
     auto load_tile = [&](const __amdgpu_buffer_rsrc_t rs, int t, u32x4 (&dst)[NP]) { load_tile_at(rs, t, dst, p_off); };
-    auto load_s_at = [&](int t, float& dst, int lane32) {   // (a key past the end of the sequence gets scale 0: it is masked anyway)
-        if (has_s) dst = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(srs, (t * kBC + lane32) * 4, 0, 0));
+    auto load_s_at = [&](int t, float& dst, int lane32, bool wanted) {   // (a key past the end of the sequence gets scale 0: it is masked anyway)
+        if (wanted) dst = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(srs, (t * kBC + lane32) * 4, 0, 0));
     };
-    auto load_s = [&](int t, float& dst) { load_s_at(t, dst, l32); };
+    auto load_s = [&](int t, float& dst) { load_s_at(t, dst, l32, has_s); };
     auto store_tile = [&](int slot_off, const int (&dsts)[NP][2], const u32x4 (&src)[NP]) {   // 16 INT8 codes -> 16 bf16 (exact)
         if (has_p) {
 #pragma unroll
@@ -381,31 +381,32 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
                 off_now[i] = p_off[i];
                 asm volatile("" : "+v"(off_now[i]));
             }
-            int l32_now = l32;
+            int l32_now = l32, w_now = w;
             asm volatile("" : "+v"(l32_now));
+            asm volatile("" : "+s"(w_now));
+            const bool has_s_now = w_now >= 2;   // (likewise: a flag kept from the top of the kernel comes back as a reload between the loads)
             load_tile_at(krs, grp, ta, off_now);
             load_tile_at(krs, 2 + grp, tb, off_now);
             load_tile_at(vrs, grp, td, off_now);
-            load_s_at(grp, sa, l32_now);
-            load_s_at(2 + grp, sb, l32_now);
-            if (grp == 0) {
-                load_tile_at(krs, 4, tc, off_now);
-                load_tile_at(vrs, 2, te, off_now);
-                load_s_at(4, sc3, l32_now);
-            }
+            load_s_at(grp, sa, l32_now, has_s_now);
+            load_s_at(2 + grp, sb, l32_now, has_s_now);
+            // (K tile 4 and V tile 2 belong to group 0's share; group 1 brings them in as well and writes the same
+            // bytes to the same place: a branch around these loads makes the compiler spill a tile that has just
+            // been asked for, and waiting for that store lets the loads after it start a memory latency late)
+            load_tile_at(krs, 4, tc, off_now);
+            load_tile_at(vrs, 2, te, off_now);
+            load_s_at(4, sc3, l32_now, has_s_now);
             load_tile_at(krs, 6 - grp, sg.k, off_now);
             load_tile_at(vrs, 4 - grp, sg.v, off_now);
-            load_s_at(6 - grp, sg.s, l32_now);
+            load_s_at(6 - grp, sg.s, l32_now, has_s_now);
             store_tile(grp * TILEBK, p_kdst, ta);
             store_tile((2 + grp) * TILEBK, p_kdst, tb);
             store_tile(grp * TILEBV, p_vdst, td);
             store_s(grp, sa);
             store_s(2 + grp, sb);
-            if (grp == 0) {
-                store_tile(4 * TILEBK, p_kdst, tc);
-                store_tile(2 * TILEBV, p_vdst, te);
-                store_s(4, sc3);
-            }
+            store_tile(4 * TILEBK, p_kdst, tc);
+            store_tile(2 * TILEBV, p_vdst, te);
+            store_s(4, sc3);
         }
         __syncthreads();
         read_q();
