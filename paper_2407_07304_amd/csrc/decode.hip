@@ -71,10 +71,15 @@ __global__ __launch_bounds__(256) void slim_decode_int8_split_kernel(
     // T_alloc is the cache's allocated length (the row stride); this sequence's first T tokens count
     const int T = kv_lens ? min(max(kv_lens[b], 1), T_alloc) : T_alloc;
     const long kvbase = ((long)b * Hkv + g) * (long)T_alloc;
-    const int8_t* kp = kc + kvbase * D + c * 16;
-    const int8_t* vp = vc + kvbase * D + c * 16;
-    const float* ksp = ks + kvbase;
-    const float* vsp = vs + kvbase;
+    // Buffer descriptors over exactly this (batch, KV head)'s first T tokens: a row past the end reads as zeros (and
+    // is masked below), an address is one 32-bit offset per lane plus a constant per row, and the descriptors live in
+    // scalar registers (with pointers and clamped row indices the addresses of a chunk's loads took some eighty
+    // vector instructions and a dozen more vector registers).
+    const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc((void*)(kc + kvbase * D), 0, (int)((unsigned)T * D), 0x00020000);
+    const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc((void*)(vc + kvbase * D), 0, (int)((unsigned)T * D), 0x00020000);
+    const __amdgpu_buffer_rsrc_t ksr = __builtin_amdgcn_make_buffer_rsrc((void*)(ks + kvbase), 0, (int)((unsigned)T * 4u), 0x00020000);
+    const __amdgpu_buffer_rsrc_t vsr = __builtin_amdgcn_make_buffer_rsrc((void*)(vs + kvbase), 0, (int)((unsigned)T * 4u), 0x00020000);
+    const int lane_off = (s * CH) * D + c * 16;   // this lane's piece of its slot's first row, relative to the chunk
     const int t_wave0 = (sp * kDecodeWaves + w) * tokens_per_wave;
     const int t_wave_end = min(T, t_wave0 + tokens_per_wave);
     const int n_chunks = t_wave0 < T ? (t_wave_end - t_wave0 + kChunk - 1) / kChunk : 0;
@@ -101,22 +106,22 @@ __global__ __launch_bounds__(256) void slim_decode_int8_split_kernel(
 
     u32x4 kbuf[CH], vbuf[CH];
     float ksc = 0.0f, vsc = 0.0f;
-    // rows past the end of the cache are clamped to the last row and masked below; the codes are read once
-    // per step, so their loads are non-temporal (measured: 5.6 -> 6.3 TB/s on the B=16, T=8192 cache)
+    // the codes are read once per step, so their loads are non-temporal (measured: 5.6 -> 6.3 TB/s on the B=16,
+    // T=8192 cache)
     auto issue_k = [&](int t_chunk0) {
+        const int off = t_chunk0 * D + lane_off;
 #pragma unroll
-        for (int it = 0; it < CH; ++it)
-            kbuf[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kp + (long)min(t_chunk0 + s * CH + it, T - 1) * D));
-        ksc = ksp[min(t_chunk0 + lane, T - 1)];
+        for (int it = 0; it < CH; ++it) kbuf[it] = __builtin_amdgcn_raw_buffer_load_b128(krs, off + it * D, 0, 2 /* nt */);
+        ksc = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(ksr, (t_chunk0 + lane) * 4, 0, 0));
     };
     auto issue_v = [&](int t_chunk0) {
+        const int off = t_chunk0 * D + lane_off;
 #pragma unroll
-        for (int it = 0; it < CH; ++it)
-            vbuf[it] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vp + (long)min(t_chunk0 + s * CH + it, T - 1) * D));
-        vsc = vsp[min(t_chunk0 + lane, T - 1)];
+        for (int it = 0; it < CH; ++it) vbuf[it] = __builtin_amdgcn_raw_buffer_load_b128(vrs, off + it * D, 0, 2 /* nt */);
+        vsc = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(vsr, (t_chunk0 + lane) * 4, 0, 0));
     };
 
-    // unconditional (a wave past the end re-reads clamped rows): keeps the prologue free of branches
+    // unconditional (a wave past the end gets zeros and reads nothing): keeps the prologue free of branches
     issue_k(t_wave0);
     issue_v(t_wave0);
     // one chunk; PREFETCH is a compile-time flag so the loop body has no branch around its loads
