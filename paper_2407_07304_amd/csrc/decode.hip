@@ -64,7 +64,7 @@ __global__ __launch_bounds__(256) void slim_decode_int8_split_kernel(
     __shared__ float lS[kDecodeWaves][SLOTS];
     __shared__ float mS[kDecodeWaves][SLOTS];
 
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // (the wave index as a scalar: everything derived from it stays uniform)
     const int c = lane % LPR, s = lane / LPR;
     const int sp = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int g = h / (Hq / Hkv);

@@ -64,7 +64,7 @@ __global__ __launch_bounds__(64 * kGqaWaves) void slim_decode_int8_gqa_kernel(
 
     __shared__ __attribute__((aligned(16))) char smem[kGqaWaves * WAVE_LDS];
 
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // (the wave index as a scalar: everything derived from it stays uniform)
     const int l32 = lane & 31, hh = lane >> 5;
     const int G = Hq / Hkv;
     const int sp = blockIdx.x * kGqaWaves + w, g = blockIdx.y, b = blockIdx.z;
@@ -98,7 +98,12 @@ __global__ __launch_bounds__(64 * kGqaWaves) void slim_decode_int8_gqa_kernel(
     // consumed): with 8 waves per compute unit that is what it takes to cover the memory latency.
     const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc((void*)(kc + kvrow0 * D), 0, (int)((unsigned)T * D), 0x00020000);
     const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc((void*)(vc + kvrow0 * D), 0, (int)((unsigned)T * D), 0x00020000);
-    const float* const sbase = (hh == 0 ? ks : vs) + kvrow0;
+    // (the scales through descriptors as well: lanes 0-31 want the K scale of token l32, lanes 32-63 the V scale; each
+    // load asks the other half's lanes for an offset past the end, which reads nothing.  A load of another kind in
+    // the loop, through a 64-bit address, makes the compiler give up counting and wait for everything in flight.)
+    const __amdgpu_buffer_rsrc_t ksr = __builtin_amdgcn_make_buffer_rsrc((void*)(ks + kvrow0), 0, (int)((unsigned)T * 4u), 0x00020000);
+    const __amdgpu_buffer_rsrc_t vsr = __builtin_amdgcn_make_buffer_rsrc((void*)(vs + kvrow0), 0, (int)((unsigned)T * 4u), 0x00020000);
+    const int s_off_k = hh == 0 ? l32 * 4 : (int)0x7ffffff0, s_off_v = hh == 1 ? l32 * 4 : (int)0x7ffffff0;
     int p_off[NP];
 #pragma unroll
     for (int n = 0; n < NP; ++n) p_off[n] = ((lane + 64 * n) / CPR) * D + ((lane + 64 * n) % CPR) * 16;
@@ -111,7 +116,9 @@ __global__ __launch_bounds__(64 * kGqaWaves) void slim_decode_int8_gqa_kernel(
     };
     auto issue_k = [&](auto par, int t0) {
         issue(par, krs, kbuf, t0);
-        sc[decltype(par)::value] = sbase[min(t0 + l32, T - 1)];
+        const uint32_t a = __builtin_amdgcn_raw_buffer_load_b32(ksr, s_off_k + t0 * 4, 0, 0);
+        const uint32_t c = __builtin_amdgcn_raw_buffer_load_b32(vsr, s_off_v + t0 * 4, 0, 0);
+        sc[decltype(par)::value] = __builtin_bit_cast(float, a | c);   // (the lanes a load left out received zero)
     };
     auto issue_v = [&](auto par, int t0) { issue(par, vrs, vbuf, t0); };
     auto stage = [&](auto par, const u32x4 (&buf)[2][NP], char* tile, int pitch) {   // widen a tile into LDS
@@ -144,33 +151,44 @@ __global__ __launch_bounds__(64 * kGqaWaves) void slim_decode_int8_gqa_kernel(
         for (int r = 0; r < 16; ++r) o[dt][r] = 0.0f;
     float M = kMasked, lsum = 0.0f;   // running max of this lane's head (log2 units), this lane's part of the row sum
 
-    if (n_tiles > 0) {
-        issue_k(std::integral_constant<int, 0>{}, t_begin);
-        issue_v(std::integral_constant<int, 0>{}, t_begin);
-    }
-    if (n_tiles > 1) {
-        issue_k(std::integral_constant<int, 1>{}, t_begin + kGqaTile);
-        issue_v(std::integral_constant<int, 1>{}, t_begin + kGqaTile);
-    }
+    // Every load of the kernel is issued unconditionally: a tile that is not wanted (past the end of this wave's
+    // run) is asked for at token T, past the end of the descriptor, so zeros arrive and no memory is read.  With the
+    // loads under a branch the compiler cannot count on them when it places its waits (on the path that skips them
+    // they are not outstanding) and waits for everything in flight at the first tile of every pair: the two tiles
+    // of loads that are meant to be in flight were then drained once per pair.
+    // The four groups keep the order the loop issues them in (K, V of a tile, then the next tile's): the compiler
+    // places the loop's waits for the worse of the two ways into the loop, and a prologue whose loads the scheduler
+    // had interleaved made that "everything in flight" at the top of every pair of tiles.
+    __builtin_amdgcn_sched_barrier(0);
+    issue_k(std::integral_constant<int, 0>{}, n_tiles > 0 ? t_begin : T);
+    __builtin_amdgcn_sched_barrier(0);
+    issue_v(std::integral_constant<int, 0>{}, n_tiles > 0 ? t_begin : T);
+    __builtin_amdgcn_sched_barrier(0);
+    issue_k(std::integral_constant<int, 1>{}, n_tiles > 1 ? t_begin + kGqaTile : T);
+    __builtin_amdgcn_sched_barrier(0);
+    issue_v(std::integral_constant<int, 1>{}, n_tiles > 1 ? t_begin + kGqaTile : T);
+    __builtin_amdgcn_sched_barrier(0);
     auto tile = [&](auto par, int i) {
         constexpr int P = decltype(par)::value;
         const int t0 = t_begin + i * kGqaTile;
-        const bool more = i + 2 < n_tiles;
+        const int t_next = i + 2 < n_tiles ? t0 + 2 * kGqaTile : T;   // (T: nothing is read, zeros arrive)
         if constexpr (TRAFFIC_ONLY) {
             u32x4 x = {0u, 0u, 0u, 0u};
 #pragma unroll
             for (int n = 0; n < NP; ++n) x ^= kbuf[P][n] ^ vbuf[P][n];
             lsum += __uint_as_float((x[0] ^ x[1] ^ x[2] ^ x[3]) & 0x3fffffffu) + sc[P];
-            if (more) {
-                issue_k(par, t0 + 2 * kGqaTile);
-                issue_v(par, t0 + 2 * kGqaTile);
-            }
+            issue_k(par, t_next);
+            issue_v(par, t_next);
+            // (each tile is consumed and refilled on its own, as in the full kernel: without this the compiler
+            // folds the two tiles of a pair into one sum and waits for both at once)
+            asm volatile("" : "+v"(lsum));
+            __builtin_amdgcn_sched_barrier(0);
             return;
         }
 
         stage(par, kbuf, kS, ROWLK);
         scS[lane] = hh == 0 ? sc[P] * scale_log2e : sc[P];
-        if (more) issue_k(par, t0 + 2 * kGqaTile);
+        issue_k(par, t_next);
 
         // scores of the tile, register r of a lane = token 8 (r/4) + 4 hh + r%4, column = head l32.  The V tile
         // is widened behind the MFMAs, which need nothing from the vector ALU while they run.
@@ -184,7 +202,7 @@ __global__ __launch_bounds__(64 * kGqaWaves) void slim_decode_int8_gqa_kernel(
         for (int s2 = 0; s2 < KS; ++s2) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s2], qB[s2], acc, 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         stage(par, vbuf, vS, ROWLV);
-        if (more) issue_v(par, t0 + 2 * kGqaTile);
+        issue_v(par, t_next);
         __builtin_amdgcn_sched_barrier(0);
 
         // softmax over the tile's tokens (the K scale multiplies the fp32 score; tokens past the end are masked)
@@ -244,9 +262,11 @@ __global__ __launch_bounds__(64 * kGqaWaves) void slim_decode_int8_gqa_kernel(
                                                                 __builtin_bit_cast(bf16x8, pw[u2]), o[dt], 0, 0, 0);
             }
     };
+    // (tiles come in pairs without a branch between them, for the same reason: a run of an odd number of tiles ends
+    // on a tile that lies past its end, whose loads asked for nothing and whose tokens are all masked)
     for (int i = 0; i < n_tiles; i += 2) {
         tile(std::integral_constant<int, 0>{}, i);
-        if (i + 1 < n_tiles) tile(std::integral_constant<int, 1>{}, i + 1);
+        tile(std::integral_constant<int, 1>{}, i + 1);
     }
 
     // this wave's split: register r of tile dt is d = 32 dt + 8 (r/4) + 4 hh + r%4 of head l32
