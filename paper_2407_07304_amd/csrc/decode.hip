@@ -116,9 +116,12 @@ __global__ __launch_bounds__(256) void slim_decode_int8_split_kernel(
     };
     auto issue_v = [&](int t_chunk0) {
         const int off = t_chunk0 * D + lane_off;
+        // (the scale first: it is wanted before the codes, and loads complete in order, so a wait for a scale
+        // issued after the codes would be a wait for the codes)
+        vsc = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(vsr, (t_chunk0 + lane) * 4, 0, 0));
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int it = 0; it < CH; ++it) vbuf[it] = __builtin_amdgcn_raw_buffer_load_b128(vrs, off + it * D, 0, 2 /* nt */);
-        vsc = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(vsr, (t_chunk0 + lane) * 4, 0, 0));
     };
 
     // unconditional (a wave past the end gets zeros and reads nothing): keeps the prologue free of branches
