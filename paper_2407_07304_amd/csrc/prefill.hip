@@ -495,10 +495,14 @@ __global__ __launch_bounds__(kPrefillThreads) void slim_prefill_kernel(const Pre
                 for (int r = 2; r < 16; r += 2) umax = fmaxf(umax, fmaxf(a[r], a[r + 1]));
                 const float m_new = fmaxf(M, half_max(umax));
                 const float alpha = fast_exp2(M - m_new);
+                // (the accumulator is still zero on a group's first tile, and on the diagonal tile the maximum has
+                // usually been met already: the 16 DT multiplications are skipped when they would change nothing)
+                if (KV_I8 || (t >= 2 && __builtin_amdgcn_ballot_w64(m_new > M) != 0)) {   // (INT8: the branch costs registers the kernel does not have)
 #pragma unroll
-                for (int dt = 0; dt < DT; ++dt)
+                    for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+                        for (int r = 0; r < 16; ++r) o[dt][r] *= alpha;
+                }
                 lsum *= alpha;
                 M = m_new;
                 float ps0 = 0.0f, ps1 = 0.0f;
