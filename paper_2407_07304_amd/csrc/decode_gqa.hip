@@ -99,8 +99,8 @@ __global__ __launch_bounds__(64 * kGqaWaves) void slim_decode_int8_gqa_kernel(
     const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc((void*)(kc + kvrow0 * D), 0, (int)((unsigned)T * D), 0x00020000);
     const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc((void*)(vc + kvrow0 * D), 0, (int)((unsigned)T * D), 0x00020000);
     // (the scales through descriptors as well: lanes 0-31 want the K scale of token l32, lanes 32-63 the V scale; each
-    // load asks the other half's lanes for an offset past the end, which reads nothing.  A load of another kind in
-    // the loop, through a 64-bit address, makes the compiler give up counting and wait for everything in flight.)
+    // load asks the other half's lanes for an offset past the end, which reads nothing, so a tile's loads are the
+    // same instructions whether the tile is wanted or not)
     const __amdgpu_buffer_rsrc_t ksr = __builtin_amdgcn_make_buffer_rsrc((void*)(ks + kvrow0), 0, (int)((unsigned)T * 4u), 0x00020000);
     const __amdgpu_buffer_rsrc_t vsr = __builtin_amdgcn_make_buffer_rsrc((void*)(vs + kvrow0), 0, (int)((unsigned)T * 4u), 0x00020000);
     const int s_off_k = hh == 0 ? l32 * 4 : (int)0x7ffffff0, s_off_v = hh == 1 ? l32 * 4 : (int)0x7ffffff0;
@@ -152,13 +152,13 @@ __global__ __launch_bounds__(64 * kGqaWaves) void slim_decode_int8_gqa_kernel(
     float M = kMasked, lsum = 0.0f;   // running max of this lane's head (log2 units), this lane's part of the row sum
 
     // Every load of the kernel is issued unconditionally: a tile that is not wanted (past the end of this wave's
-    // run) is asked for at token T, past the end of the descriptor, so zeros arrive and no memory is read.  With the
-    // loads under a branch the compiler cannot count on them when it places its waits (on the path that skips them
-    // they are not outstanding) and waits for everything in flight at the first tile of every pair: the two tiles
-    // of loads that are meant to be in flight were then drained once per pair.
-    // The four groups keep the order the loop issues them in (K, V of a tile, then the next tile's): the compiler
-    // places the loop's waits for the worse of the two ways into the loop, and a prologue whose loads the scheduler
-    // had interleaved made that "everything in flight" at the top of every pair of tiles.
+    // run) is asked for at token T, past the end of the descriptor, so zeros arrive and no memory is read.  The
+    // compiler places a wait by counting the loads issued after the one it needs, along the worst path that leads
+    // there; loads under a branch are not outstanding on the path that skips them, and at the loop's head the
+    // worst path may be the one from the prologue.  So the prologue's four groups keep the order the loop issues
+    // them in (K, V of a tile, then the next tile's): with the sixteen loads interleaved by the scheduler, the first
+    // tile's K came last, and the loop began every pair of tiles by waiting for everything in flight, which
+    // drained the two tiles of loads that are meant to stay in flight.
     __builtin_amdgcn_sched_barrier(0);
     issue_k(std::integral_constant<int, 0>{}, n_tiles > 0 ? t_begin : T);
     __builtin_amdgcn_sched_barrier(0);
