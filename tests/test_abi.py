@@ -103,6 +103,20 @@ def test_decode_rejects_bad_arguments_and_reports_workspace(lib):
     assert call(wsb=ws(1, 2, 2, 100, 128) - 1) == 5
 
 
+def test_decode_workspace_is_a_whole_number_of_split_records_for_every_geometry(lib):
+    """Host logic only: whatever split geometry the library picks (per-head or grouped-query kernel), the workspace
+    is n_split records of (max, sum, accumulator[D]) per (batch, query head), with at least one split and never
+    more splits than the cache has 32-token tiles (plus the one a two-wave workgroup may leave empty)."""
+    ws = lib.slim_attn_decode_int8_workspace_bytes
+    for D in (64, 128):
+        for (B, Hq, Hkv) in ((1, 1, 1), (1, 32, 32), (16, 32, 32), (16, 64, 8), (3, 40, 1), (64, 8, 8), (2, 64, 2), (1, 8, 4)):
+            for T in (1, 31, 32, 33, 100, 2048, 8191, 8192, 32768, 100000):
+                n, rec = ws(B, Hq, Hkv, T, D), B * Hq * (D + 2) * 4
+                assert n > 0 and n % rec == 0, (B, Hq, Hkv, T, D, n)
+                splits = n // rec
+                assert 1 <= splits <= (T + 31) // 32 + 1, (B, Hq, Hkv, T, D, splits)
+
+
 def test_varlen_decode_rejects_bad_arguments(lib):
     f = lib.slim_attn_decode_int8_varlen
 
